@@ -1,0 +1,222 @@
+"""CPU oracle of the verification hot path -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this package.  It shares no code with the HIP library and never imports it.
+
+The arithmetic lives in ``faser_oracle.c`` (plain C, fp64, one loop per sum); this module
+compiles it with gcc, marshals numpy arrays, and spells out the chunked (frontier)
+verification schedule of Sec. 3.3 of the paper in python loops on top of the C steps.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "faser_oracle.c")
+_LIB = os.path.join(_HERE, "libfaser_oracle.so")
+_lib = None
+
+F32, BF16 = 0, 1
+PROBS, LOGITS = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over independent outputs only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def n_threads() -> int:
+    """Host threads the oracle's OpenMP loops use."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        try:
+            return int(env.split(",")[0])
+        except ValueError:
+            pass
+    return os.cpu_count() or 1
+
+
+def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, H_q, H_kv, D, P, dtype, scale):
+    """Sec. 2.1 verification attention over the paged cache; returns (out[N,H_q,D], lse[N,H_q]) in fp64."""
+    lib = _load()
+    code = BF16 if dtype == "bf16" else F32
+    st = np.uint16 if code == BF16 else np.float32
+    q, k_cache, v_cache = _c(q, st), _c(k_cache, st), _c(v_cache, st)
+    bt, ctx, cu = _c(block_tables, np.int32), _c(ctx_lens, np.int32), _c(cu_q, np.int32)
+    B = len(ctx)
+    N = int(cu[-1])
+    out = np.zeros((N, H_q, D), dtype=np.float64)
+    lse = np.zeros((N, H_q), dtype=np.float64)
+    rc = lib.fo_verify_attention(_p(q), _p(k_cache), _p(v_cache), _p(bt), _p(ctx), _p(cu), _p(out), _p(lse),
+                                 ctypes.c_int(B), ctypes.c_int(H_q), ctypes.c_int(H_kv), ctypes.c_int(D),
+                                 ctypes.c_int(P), ctypes.c_int(bt.shape[1]), ctypes.c_int(code),
+                                 ctypes.c_double(scale))
+    if rc != 0:
+        raise ValueError(f"fo_verify_attention: {rc}")
+    return out, lse
+
+
+def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, *, S_max,
+                t_rows=None, d_rows=None, mode=PROBS, temperature=1.0):
+    """Sec. 2.1 accept-until-first-mismatch with recovery/bonus token.
+
+    Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo[B], cdf_hi[B]).
+    """
+    lib = _load()
+    p_target, p_draft = _c(p_target, np.float32), _c(p_draft, np.float32)
+    V = p_target.shape[1]
+    toks, ua, us = _c(draft_tokens, np.int32), _c(u_accept, np.float32), _c(u_sample, np.float32)
+    cu_t, cu_d = _c(cu_t, np.int32), _c(cu_d, np.int32)
+    tr = None if t_rows is None else _c(t_rows, np.int32)
+    dr = None if d_rows is None else _c(d_rows, np.int32)
+    B = len(cu_t) - 1
+    acc = np.zeros(B, np.int32)
+    nem = np.zeros(B, np.int32)
+    em = np.full((B, S_max + 1), -1, np.int32)
+    lo = np.full(B, np.nan)
+    hi = np.full(B, np.nan)
+    rc = lib.fo_spec_accept(_p(p_target), _p(p_draft), _p(toks), _p(ua), _p(us), _p(cu_t), _p(cu_d), _p(tr), _p(dr),
+                            _p(acc), _p(nem), _p(em), _p(lo), _p(hi), ctypes.c_int(B), ctypes.c_int(V),
+                            ctypes.c_int(S_max), ctypes.c_int(mode), ctypes.c_double(temperature))
+    if rc != 0:
+        raise ValueError(f"fo_spec_accept: {rc}")
+    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=lo, cdf_hi=hi)
+
+
+def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None):
+    """Sec. 3.2 / 3.3 row pruning; returns dict of the new ragged layout and row maps."""
+    lib = _load()
+    keep, cu = _c(keep_mask, np.uint8), _c(cu_q, np.int32)
+    B = len(cu) - 1
+    N = int(cu[-1])
+    assert len(keep) == N
+    new_cu = np.zeros(B + 1, np.int32)
+    new_len = np.zeros(B, np.int32)
+    src = np.full(N, -1, np.int32)
+    dst = np.full(N, -1, np.int32)
+    n_act = np.zeros(1, np.int32)
+    act = np.full(B, -1, np.int32)
+    pin = pout = None
+    row_bytes = 0
+    if payload is not None:
+        pay = np.ascontiguousarray(payload)
+        assert pay.shape[0] == N
+        row_bytes = pay.nbytes // max(N, 1) if N else 0
+        pin = pay.view(np.uint8).reshape(N, -1) if N else np.zeros((0, 0), np.uint8)
+        pout = np.zeros_like(pin)
+    lib.fo_prune_compact(_p(keep), _p(cu), _p(new_cu), _p(new_len), _p(src), _p(dst), _p(n_act), _p(act),
+                         _p(pin), _p(pout), ctypes.c_int64(row_bytes), ctypes.c_int(B),
+                         ctypes.c_int(1 if suffix_close else 0))
+    res = dict(new_cu_q=new_cu, new_q_lens=new_len, src_row=src, dst_row=dst, n_active=int(n_act[0]),
+               active_ids=act)
+    if payload is not None:
+        n_new = int(new_cu[-1])
+        res["payload"] = pout.view(pay.dtype).reshape((N,) + pay.shape[1:])[:n_new]
+    return res
+
+
+def prune_restore(compact, dst_row, *, pad_byte=0):
+    """Sec. 3.2 / Sec. 4: scatter compacted rows back to the original layout."""
+    lib = _load()
+    dst = _c(dst_row, np.int32)
+    N = len(dst)
+    comp = np.ascontiguousarray(compact)
+    row_shape = comp.shape[1:]
+    row_bytes = int(np.prod(row_shape)) * comp.dtype.itemsize
+    cin = comp.view(np.uint8).reshape(comp.shape[0], -1)
+    out = np.zeros((N, row_bytes), np.uint8)
+    has = np.zeros(N, np.uint8)
+    lib.fo_prune_restore(_p(cin), _p(dst), _p(out), _p(has), ctypes.c_int64(row_bytes), ctypes.c_int(N),
+                         ctypes.c_int(pad_byte))
+    return out.view(comp.dtype).reshape((N,) + row_shape), has
+
+
+def verify_chunked(batch, chunks: List[np.ndarray], *, with_attention=True, mode=PROBS, temperature=1.0):
+    """Frontier (chunked) verification of one step, Sec. 3.3.
+
+    ``chunks[k][i]`` is the number of drafts of request i verified in chunk k.  A request's
+    bonus row rides with the chunk that verifies its last draft (or with chunk 0 when it
+    has no drafts).  After every chunk the accept step runs on that chunk's rows; a request
+    with a rejection commits its accepted prefix and recovery token and every later row of
+    it is discarded, so later chunks hold no row of it.
+
+    Returns dict(accepted_len, n_emitted, emitted [B,S_max+1], rows_processed, and, with
+    attention, out [N,H_q,D] with NaN on rows that were never computed).
+    """
+    B, S_max = batch.B, batch.S_max
+    cu_q, cu_d = batch.cu_q, batch.cu_d
+    N = batch.N
+    pos = np.zeros(B, np.int64)
+    active = np.ones(B, bool)
+    acc_total = np.zeros(B, np.int32)
+    n_em = np.zeros(B, np.int32)
+    emitted = np.full((B, S_max + 1), -1, np.int32)
+    out = np.full((N, batch.H_q, batch.D), np.nan) if with_attention else None
+    rows_processed = 0
+    p_src = batch.z_target if mode == LOGITS else batch.p_target
+    q_src = batch.z_draft if mode == LOGITS else batch.p_draft
+    for k, nk in enumerate(chunks):
+        nk = np.asarray(nk, np.int64)
+        t_mask = np.zeros(N, np.uint8)
+        d_mask = np.zeros(batch.N_d, np.uint8)
+        ctx_k = batch.ctx_lens.copy()
+        for i in range(B):
+            if not active[i]:
+                continue
+            last = pos[i] + nk[i] == batch.spec_lens[i]
+            first_and_empty = batch.spec_lens[i] == 0 and k == 0
+            t_i = int(nk[i]) + (1 if (last and (nk[i] > 0 or first_and_empty)) else 0)
+            t_mask[cu_q[i] + pos[i]: cu_q[i] + pos[i] + t_i] = 1
+            d_mask[cu_d[i] + pos[i]: cu_d[i] + pos[i] + nk[i]] = 1
+            ctx_k[i] = batch.ctx_lens[i] + pos[i]
+        tsel = prune_compact(t_mask, cu_q, suffix_close=False, payload=batch.q if with_attention else None)
+        dsel = prune_compact(d_mask, cu_d, suffix_close=False)
+        n_rows = int(tsel["new_cu_q"][-1])
+        rows_processed += n_rows
+        if n_rows == 0:
+            continue
+        if with_attention:
+            o_k, _ = verify_attention(tsel["payload"], batch.k_cache, batch.v_cache, batch.block_tables, ctx_k,
+                                      tsel["new_cu_q"], H_q=batch.H_q, H_kv=batch.H_kv, D=batch.D, P=batch.P,
+                                      dtype=batch.dtype, scale=batch.scale)
+            out[tsel["src_row"][:n_rows]] = o_k
+        S_k = int(nk.max()) if len(nk) else 0
+        r = spec_accept(p_src, q_src, batch.draft_tokens, batch.u_accept, batch.u_sample, tsel["new_cu_q"],
+                        dsel["new_cu_q"], S_max=S_k, t_rows=tsel["src_row"][:n_rows],
+                        d_rows=dsel["src_row"][: int(dsel["new_cu_q"][-1])], mode=mode, temperature=temperature)
+        for i in range(B):
+            if not active[i]:
+                continue
+            ne = int(r["n_emitted"][i])
+            emitted[i, n_em[i]: n_em[i] + ne] = r["emitted"][i, :ne]
+            n_em[i] += ne
+            acc_total[i] += r["accepted_len"][i]
+            if r["accepted_len"][i] < nk[i]:
+                active[i] = False
+            pos[i] += nk[i]
+            if pos[i] >= batch.spec_lens[i]:
+                active[i] = False
+    return dict(accepted_len=acc_total, n_emitted=n_em, emitted=emitted, rows_processed=rows_processed, out=out)
