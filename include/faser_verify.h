@@ -1,0 +1,249 @@
+/*
+ * faser_verify -- target-side verification step of speculative decoding over a continuous
+ * batch in which every request carries its own speculative length (FASER, arXiv
+ * 2604.20503, Sec. 3.1), as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * One verification step is
+ *     fsr_verify_attention  (once per transformer layer)
+ *  -> fsr_spec_accept       (on the step's target / draft distributions)
+ *  -> fsr_prune_compact     (drop rejected rows, re-pack the ragged batch)
+ * and, for frontier (chunked) verification (Sec. 3.3), fsr_frontier_plan /
+ * fsr_frontier_commit carry the per-request state from one chunk to the next without a
+ * host round trip.
+ *
+ * Conventions for every entry point
+ *   - Returns 0 (FSR_OK) or a negative FSR_E* code; fsr_last_error() gives a static,
+ *     thread-local description of the last failure.  Nothing throws or aborts.
+ *   - Every pointer argument is DEVICE memory owned by the caller unless its comment says
+ *     "host".  The library reads the inputs and writes only the named outputs and the
+ *     workspace.  Nothing is allocated or freed by these calls.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  No call synchronises the stream or the device.  Calls on one stream may
+ *     share a workspace; calls that can overlap on different streams must not.
+ *   - Ragged metadata (lengths, offsets, masks) lives on the device; the only host scalars
+ *     are static shapes and capacities.  Host-detectable errors (null pointers, bad
+ *     shapes, unsupported dtype/head_dim, workspace too small) are reported before
+ *     anything is launched.
+ *   - Ragged layout: request i owns rows cu[i] .. cu[i+1]-1 of the row-major arrays; a
+ *     request with zero rows is legal everywhere and costs nothing.
+ */
+#ifndef FASER_VERIFY_H
+#define FASER_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FSR_OK 0
+#define FSR_EINVAL (-1) /* null pointer or out-of-range scalar argument */
+#define FSR_ESHAPE (-2) /* inconsistent sizes */
+#define FSR_EUNSUP (-3) /* dtype / head_dim / page size combination not built */
+#define FSR_EWS (-4)    /* workspace missing or too small */
+#define FSR_EHIP (-5)   /* HIP runtime error at launch */
+
+enum { FSR_F32 = 0, FSR_BF16 = 1 };
+enum { FSR_PROBS = 0, FSR_LOGITS = 1 };
+
+/* Static shape of one attention call. */
+typedef struct fsr_attn_params {
+    int32_t B;         /* requests in the batch (>= 0) */
+    int32_t N_cap;     /* rows allocated in q/out; cu_q[B] <= N_cap */
+    int32_t H_q;       /* query heads */
+    int32_t H_kv;      /* KV heads, H_q % H_kv == 0 */
+    int32_t D;         /* head dim: 64 or 128 */
+    int32_t P;         /* tokens per KV page: 16 */
+    int32_t max_pages; /* row stride of block_tables */
+    int32_t n_pages;   /* pages in the caches (page ids are clamped into [0, n_pages)) */
+    int32_t dtype;     /* FSR_F32 or FSR_BF16: element type of q, k_cache, v_cache */
+    int32_t out_dtype; /* element type of out: FSR_F32 always allowed; FSR_BF16 with bf16 inputs */
+    float scale;       /* softmax scale, normally 1/sqrt(D) */
+    int32_t max_q_len; /* upper bound on the rows of any one request in this call (speculative
+                          length + 1), or 0 if unknown.  A performance hint only: it picks the
+                          register budget of the kernel; requests with more rows are still
+                          computed correctly, in several passes over their keys. */
+    int32_t reserved;  /* must be 0 */
+} fsr_attn_params;
+
+/* Static shape of one accept call. */
+typedef struct fsr_accept_params {
+    int32_t B;         /* requests */
+    int32_t V;         /* vocabulary size (> 0) */
+    int32_t S_max;     /* max drafts per request in this call; emitted has S_max+1 columns */
+    int32_t mode;      /* FSR_PROBS: rows are probabilities; FSR_LOGITS: rows are logits */
+    double temperature; /* LOGITS mode: p = softmax(z / temperature), > 0; ignored in PROBS mode */
+    int32_t reserved;  /* must be 0 */
+    int32_t reserved2; /* must be 0 */
+} fsr_accept_params;
+
+/* Static shape of one compaction call. */
+typedef struct fsr_prune_params {
+    int32_t B;            /* requests */
+    int32_t N_cap;        /* rows allocated in keep_mask / src_row / dst_row; cu_q[B] <= N_cap */
+    int32_t suffix_close; /* 1: a request keeps its leading run of kept rows; 0: any subset, order kept */
+    int32_t reserved;     /* must be 0 */
+} fsr_prune_params;
+
+/* Static description of the last failure on the calling thread ("" if none).  Host. */
+const char* fsr_last_error(void);
+
+/* Library version string.  Host. */
+const char* fsr_version(void);
+
+/*
+ * Workspace bytes needed by fsr_verify_attention for shapes up to *p (host query, no GPU
+ * work).  The same size covers every smaller B / N_cap / max_pages with the same heads.
+ */
+int fsr_attn_workspace_bytes(const fsr_attn_params* p /*host*/, size_t* out_bytes /*host*/);
+
+/*
+ * Verification attention (Sec. 2.1: the target model verifies all drafted tokens of a
+ * request in one parallel pass; Sec. 3.1: each request has its own speculative length).
+ *
+ * For request i with c = ctx_lens[i] committed tokens and q_i = cu_q[i+1]-cu_q[i] rows in
+ * this call, row j (0 <= j < q_i) is the query of the token at logical position c + j and
+ * attends to positions 0 .. c + j (causal inside the suffix):
+ *     out[row, h, :] = softmax_t(scale * q[row, h, :] . K_i[t, h/G, :]) . V_i[t, h/G, :]
+ * with G = H_q / H_kv.  The K/V of the call's own rows must already be in the cache.
+ * Logical position t of request i is stored in page block_tables[i*max_pages + t/P], slot
+ * t % P.
+ *
+ *   q            [N_cap, H_q, D]      dtype
+ *   k_cache      [n_pages, H_kv, P, D] dtype       v_cache likewise
+ *   block_tables [B, max_pages] int32 (entries beyond a request's last page are not read)
+ *   ctx_lens     [B] int32   tokens cached BEFORE this call's first row of the request
+ *   spec_lens    [B] int32   nullable, carried for the caller's bookkeeping; cu_q decides
+ *                            the number of rows (a one-shot call has spec_lens[i]+1 rows)
+ *   cu_q         [B+1] int32 row offsets
+ *   out          [N_cap, H_q, D] out_dtype; rows >= cu_q[B] are not written
+ *   lse          [N_cap, H_q] float32, nullable: natural-log sum of exp of the scaled scores
+ *   workspace    >= fsr_attn_workspace_bytes(p) bytes, 256-byte aligned
+ * Softmax and accumulation are fp32; bf16 probabilities are carried as a hi+lo pair into
+ * the matrix cores so the result is accurate to fp32 rounding, not bf16.
+ */
+int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* block_tables, const int32_t* ctx_lens,
+                         const int32_t* spec_lens, const int32_t* cu_q, void* out, float* lse,
+                         const fsr_attn_params* p /*host*/, void* workspace, size_t ws_bytes,
+                         void* stream);
+
+/* Workspace bytes needed by fsr_spec_accept for shapes up to *p (host query). */
+int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_bytes /*host*/);
+
+/*
+ * Accept / reject with recovery or bonus token (Sec. 2.1: accept drafted tokens until the
+ * first mismatch, discard the rejected suffix, resample the first mismatched token from
+ * the target; Sec. 3.3: "recovery token").  The mismatch test is that of speculative
+ * sampling: draft x_n is accepted iff u_accept * q_n(x_n) < p_n(x_n) (evaluated in fp64).
+ *
+ * Request i has d_i = cu_d[i+1]-cu_d[i] draft rows and t_i = cu_t[i+1]-cu_t[i] target
+ * rows, t_i - d_i in {0, 1}: the extra target row is the bonus row.
+ *   n = number of leading accepted drafts.
+ *   n < d_i            : one token from max(p_n - q_n, 0) normalised (from p_n if that is 0)
+ *   n == d_i, bonus row: one token from p_{d_i}
+ *   n == d_i, no bonus : no extra token (non-final frontier chunk, or rows pruned away)
+ * Tokens are drawn by inverse CDF in index order with u_sample[i]: the first token whose
+ * running mass (fp64) is strictly greater than u_sample[i] * total mass; zero-mass tokens
+ * are never drawn.  The library draws no random numbers itself.
+ *
+ *   p_target     [*, V] float32 (probabilities, or logits in FSR_LOGITS mode)
+ *   p_draft      [*, V] float32
+ *   draft_tokens [*] int32, u_accept [*] float32 in [0,1): indexed like p_draft rows
+ *   u_sample     [B] float32 in [0,1)
+ *   cu_t, cu_d   [B+1] int32 offsets of the call's target / draft rows
+ *   t_rows       nullable [cu_t[B]] int32: call target row r is storage row t_rows[r] of
+ *                p_target (identity if null)
+ *   d_rows       nullable [cu_d[B]] int32: call draft row r is storage row d_rows[r] of
+ *                p_draft, draft_tokens and u_accept (identity if null).  These maps are
+ *                what fsr_prune_compact returns as src_row.
+ *   accepted_len [B] int32 (n), n_emitted [B] int32, emitted [B, S_max+1] int32 padded -1
+ * Requests with d_i > S_max or t_i - d_i outside {0,1} get accepted_len = n_emitted = -1.
+ * Draft token ids are clamped into [0, V).
+ */
+int fsr_spec_accept(const float* p_target, const float* p_draft, const int32_t* draft_tokens,
+                    const float* u_accept, const float* u_sample, const int32_t* cu_t,
+                    const int32_t* cu_d, const int32_t* t_rows, const int32_t* d_rows,
+                    int32_t* accepted_len, int32_t* n_emitted, int32_t* emitted,
+                    const fsr_accept_params* p /*host*/, void* workspace, size_t ws_bytes,
+                    void* stream);
+
+/*
+ * Pruning of rejected rows and re-packing of the ragged batch (Sec. 3.2: the next layer
+ * prunes the tokens of the rejected suffix and only the remaining tokens proceed;
+ * Sec. 3.3: on a rejection every speculative token beyond it is discarded).
+ *
+ *   keep_mask  [N_cap] uint8 (non-zero = keep), cu_q [B+1] int32
+ *   new_cu_q   [B+1] int32, new_q_lens [B] int32
+ *   src_row    [N_cap] int32: new row -> old row for the first new_cu_q[B] entries, -1 after
+ *   dst_row    [N_cap] int32: old row -> new row, -1 if dropped (rows >= cu_q[B]: -1)
+ *   n_active   [1] int32, active_ids [B] int32: ascending requests with >= 1 kept row, -1 after
+ *   payload_in nullable [N_cap, row_bytes]; payload_out [N_cap, row_bytes] gets the kept
+ *              rows as a dense prefix (rows beyond it are not written).  row_bytes % 4 == 0.
+ * No workspace is needed.
+ */
+int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, int32_t* new_cu_q,
+                      int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row, int32_t* n_active,
+                      int32_t* active_ids, const void* payload_in, void* payload_out,
+                      size_t row_bytes, const fsr_prune_params* p /*host*/, void* stream);
+
+/*
+ * Inverse of the compaction (Sec. 3.2: pruned positions are restored to the original
+ * layout before logits; Sec. 4: pruned tensors are padded back to their original shapes).
+ * restored[r] = compact[dst_row[r]] where dst_row[r] >= 0, else every 32-bit word of the
+ * row is pad_word; has_value[r] (nullable, uint8) says which.  row_bytes % 4 == 0.
+ */
+int fsr_prune_restore(const void* compact, const int32_t* dst_row, void* restored,
+                      uint8_t* has_value, size_t row_bytes, int32_t N, uint32_t pad_word,
+                      void* stream);
+
+/*
+ * Partial restore (Sec. 3.2, same passage): out[src_row[r]] = compact[r] for r < n_rows[0];
+ * rows of `out` that no compacted row maps to keep their contents.  Used to put one chunk's
+ * rows back into the original layout while other chunks' rows stay.  src_row [N_cap] and
+ * n_rows [1] are fsr_prune_compact's src_row and &new_cu_q[B].  row_bytes % 4 == 0.
+ */
+int fsr_prune_scatter(const void* compact, const int32_t* src_row, const int32_t* n_rows, void* out,
+                      size_t row_bytes, int32_t N_cap, void* stream);
+
+/*
+ * Frontier (chunked) verification state machine, Sec. 3.3: the suffix of every request is
+ * verified in chunks; accepted tokens are committed per chunk; a rejection commits the
+ * accepted prefix and the recovery token and discards every later speculative token of
+ * that request.
+ *
+ * Per-request device state (all [B] int32, caller-allocated, set up by fsr_frontier_init):
+ *   pos[i]     drafts of request i already verified;  active[i] 1 while it has rows left
+ *   n_out[i]   tokens committed so far this step;  out_tokens [B, S_total_max+1] int32
+ *
+ * fsr_frontier_plan builds chunk k's row selections over the ORIGINAL row layout:
+ *   chunk_len  [B] int32: drafts of request i to verify in this chunk (0 allowed)
+ *   t_mask [N_t] uint8 over target/query rows (cu_q layout; the bonus row rides with the
+ *   chunk that verifies the request's last draft), d_mask [N_d] uint8 over draft rows
+ *   (cu_d layout), chunk_ctx [B] int32 = ctx_lens[i] + pos[i].
+ * Feed the masks to fsr_prune_compact (suffix_close = 0) to get the chunk's offsets, row
+ * maps and gathered q rows.
+ *
+ * fsr_frontier_commit consumes the chunk's accept results: appends emitted tokens to
+ * out_tokens, advances pos by chunk_len, and clears active for requests that saw a
+ * rejection or have no drafts left.
+ */
+int fsr_frontier_init(const int32_t* spec_lens, int32_t* pos, int32_t* active, int32_t* n_out,
+                      int32_t* acc_total, int32_t* out_tokens, int32_t B, int32_t out_stride,
+                      void* stream);
+int fsr_frontier_plan(const int32_t* ctx_lens, const int32_t* spec_lens, const int32_t* cu_q,
+                      const int32_t* cu_d, const int32_t* pos, const int32_t* active,
+                      const int32_t* chunk_len, uint8_t* t_mask, uint8_t* d_mask,
+                      int32_t* chunk_ctx, int32_t B, int32_t N_t_cap, int32_t N_d_cap,
+                      void* stream);
+int fsr_frontier_commit(const int32_t* spec_lens, const int32_t* chunk_len,
+                        const int32_t* accepted_len, const int32_t* n_emitted,
+                        const int32_t* emitted, int32_t emitted_stride, int32_t* pos,
+                        int32_t* active, int32_t* n_out, int32_t* acc_total, int32_t* out_tokens,
+                        int32_t B, int32_t out_stride, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASER_VERIFY_H */

@@ -1,0 +1,288 @@
+"""ctypes binding of the C ABI declared in ``include/faser_verify.h``.
+
+Argument marshalling only: tensors are checked for device, dtype and contiguity and handed
+over as raw pointers together with the current HIP stream.  No arithmetic happens here and
+there is no fallback: if the library is missing, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfaser_verify.so")
+_lib = None
+
+F32, BF16 = 0, 1
+PROBS, LOGITS = 0, 1
+
+SYMBOLS = [
+    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention",
+    "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
+    "fsr_prune_scatter", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
+]
+
+
+class FsrError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"faser_verify error {code}: {msg}")
+        self.code = code
+
+
+class AttnParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "N_cap", "H_q", "H_kv", "D", "P", "max_pages", "n_pages", "dtype", "out_dtype")] + \
+               [("scale", ctypes.c_float), ("max_q_len", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class AcceptParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("S_max", ctypes.c_int32), ("mode", ctypes.c_int32),
+                ("temperature", ctypes.c_double), ("reserved", ctypes.c_int32), ("reserved2", ctypes.c_int32)]
+
+
+class PruneParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("N_cap", ctypes.c_int32), ("suffix_close", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load ``libfaser_verify.so``; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python paper_2604_20503_amd/build.py` "
+                "(there is no CPU or PyTorch fallback for the verification kernels)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        lib.fsr_last_error.restype = ctypes.c_char_p
+        lib.fsr_version.restype = ctypes.c_char_p
+        for name in SYMBOLS[2:]:
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def version() -> str:
+    return load_library().fsr_version().decode()
+
+
+def last_error() -> str:
+    return load_library().fsr_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise FsrError(rc, last_error())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return F32
+    if dt == torch.bfloat16:
+        return BF16
+    raise ValueError(f"unsupported dtype {dt}")
+
+
+def _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len) -> AttnParams:
+    N_cap, H_q, D = q.shape
+    n_pages, H_kv, P, D2 = k_cache.shape
+    if D2 != D:
+        raise ValueError("head dim of q and k_cache differ")
+    return AttnParams(B=B, N_cap=N_cap, H_q=H_q, H_kv=H_kv, D=D, P=P, max_pages=block_tables.shape[1],
+                      n_pages=n_pages, dtype=_code(q.dtype), out_dtype=_code(out_dtype), scale=float(scale),
+                      max_q_len=int(max_q_len), reserved=0)
+
+
+def attn_workspace_bytes(*, B, N_cap, H_q, H_kv, D, P, max_pages, n_pages, dtype, out_dtype, scale=1.0,
+                         max_q_len=0) -> int:
+    p = AttnParams(B=B, N_cap=N_cap, H_q=H_q, H_kv=H_kv, D=D, P=P, max_pages=max_pages, n_pages=n_pages,
+                   dtype=_code(dtype), out_dtype=_code(out_dtype), scale=float(scale), max_q_len=int(max_q_len),
+                   reserved=0)
+    out = ctypes.c_size_t(0)
+    _check(load_library().fsr_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
+    return int(out.value)
+
+
+def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_q, *, scale, out=None, lse=None,
+                     out_dtype=None, workspace=None, max_q_len=0):
+    """fsr_verify_attention.  q [N_cap,H_q,D]; caches [n_pages,H_kv,P,D]; returns (out, lse)."""
+    lib = load_library()
+    B = ctx_lens.shape[0]
+    out_dtype = out_dtype or (out.dtype if out is not None else q.dtype)
+    p = _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len)
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype, device=q.device)
+    if v_cache.shape != k_cache.shape or v_cache.dtype != k_cache.dtype or k_cache.dtype != q.dtype:
+        raise ValueError("q, k_cache and v_cache must share dtype; caches must share shape")
+    if cu_q.shape[0] != B + 1 or block_tables.shape[0] != B:
+        raise ValueError("cu_q must have B+1 entries and block_tables B rows")
+    need = ctypes.c_size_t(0)
+    _check(lib.fsr_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(need)))
+    if workspace is None and need.value:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.fsr_verify_attention(
+        _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+        _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+        _ptr(spec_lens, torch.int32, "spec_lens"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"),
+        _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _ptr(workspace, name="workspace"),
+        ctypes.c_size_t(ws_bytes), _stream()))
+    return out, lse
+
+
+def accept_workspace_bytes(*, B, V, S_max, mode=PROBS, temperature=1.0) -> int:
+    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), reserved=0, reserved2=0)
+    out = ctypes.c_size_t(0)
+    _check(load_library().fsr_accept_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
+    return int(out.value)
+
+
+def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, *, S_max, t_rows=None, d_rows=None,
+                mode=PROBS, temperature=1.0, accepted_len=None, n_emitted=None, emitted=None, workspace=None):
+    """fsr_spec_accept.  Returns (accepted_len [B], n_emitted [B], emitted [B, S_max+1])."""
+    lib = load_library()
+    B = u_sample.shape[0]
+    V = p_target.shape[1]
+    dev = p_target.device
+    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), reserved=0, reserved2=0)
+    if accepted_len is None:
+        accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if n_emitted is None:
+        n_emitted = torch.empty(B, dtype=torch.int32, device=dev)
+    if emitted is None:
+        emitted = torch.empty((B, S_max + 1), dtype=torch.int32, device=dev)
+    if emitted.shape != (B, S_max + 1):
+        raise ValueError("emitted must be [B, S_max+1]")
+    if cu_t.shape[0] != B + 1 or cu_d.shape[0] != B + 1:
+        raise ValueError("cu_t and cu_d must have B+1 entries")
+    need = ctypes.c_size_t(0)
+    _check(lib.fsr_accept_workspace_bytes(ctypes.byref(p), ctypes.byref(need)))
+    if workspace is None:
+        workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.fsr_spec_accept(
+        _ptr(p_target, torch.float32, "p_target"), _ptr(p_draft, torch.float32, "p_draft"),
+        _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(u_accept, torch.float32, "u_accept"),
+        _ptr(u_sample, torch.float32, "u_sample"), _ptr(cu_t, torch.int32, "cu_t"), _ptr(cu_d, torch.int32, "cu_d"),
+        _ptr(t_rows, torch.int32, "t_rows"), _ptr(d_rows, torch.int32, "d_rows"),
+        _ptr(accepted_len, torch.int32, "accepted_len"), _ptr(n_emitted, torch.int32, "n_emitted"),
+        _ptr(emitted, torch.int32, "emitted"), ctypes.byref(p), _ptr(workspace, name="workspace"),
+        ctypes.c_size_t(ws_bytes), _stream()))
+    return accepted_len, n_emitted, emitted
+
+
+def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None, payload_out=None, out=None):
+    """fsr_prune_compact.  Returns dict(new_cu_q, new_q_lens, src_row, dst_row, n_active, active_ids[, payload])."""
+    lib = load_library()
+    B = cu_q.shape[0] - 1
+    N_cap = keep_mask.shape[0]
+    dev = cu_q.device
+    p = PruneParams(B=B, N_cap=N_cap, suffix_close=1 if suffix_close else 0, reserved=0)
+    o = out or {}
+    i32 = dict(dtype=torch.int32, device=dev)
+    new_cu_q = o.get("new_cu_q", None)
+    if new_cu_q is None:
+        new_cu_q = torch.empty(B + 1, **i32)
+    new_q_lens = o.get("new_q_lens") if "new_q_lens" in o else torch.empty(B, **i32)
+    src_row = o.get("src_row") if "src_row" in o else torch.empty(N_cap, **i32)
+    dst_row = o.get("dst_row") if "dst_row" in o else torch.empty(N_cap, **i32)
+    n_active = o.get("n_active") if "n_active" in o else torch.empty(1, **i32)
+    active_ids = o.get("active_ids") if "active_ids" in o else torch.empty(B, **i32)
+    row_bytes = 0
+    if payload is not None:
+        if payload.shape[0] != N_cap:
+            raise ValueError("payload must have N_cap rows")
+        row_bytes = (payload.numel() // max(N_cap, 1)) * payload.element_size() if N_cap else 0
+        if payload_out is None:
+            payload_out = torch.empty_like(payload)
+    _check(lib.fsr_prune_compact(
+        _ptr(keep_mask, torch.uint8, "keep_mask"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(new_cu_q, torch.int32),
+        _ptr(new_q_lens, torch.int32), _ptr(src_row, torch.int32), _ptr(dst_row, torch.int32),
+        _ptr(n_active, torch.int32), _ptr(active_ids, torch.int32),
+        _ptr(payload if row_bytes else None, name="payload"), _ptr(payload_out if row_bytes else None, name="payload_out"),
+        ctypes.c_size_t(row_bytes), ctypes.byref(p), _stream()))
+    res = dict(new_cu_q=new_cu_q, new_q_lens=new_q_lens, src_row=src_row, dst_row=dst_row, n_active=n_active,
+               active_ids=active_ids)
+    if payload is not None:
+        res["payload"] = payload_out
+    return res
+
+
+def prune_restore(compact, dst_row, *, pad_word=0, restored=None, has_value=None):
+    """fsr_prune_restore.  Returns (restored [N, ...], has_value [N] uint8)."""
+    lib = load_library()
+    N = dst_row.shape[0]
+    row_shape = tuple(compact.shape[1:])
+    if restored is None:
+        restored = torch.empty((N,) + row_shape, dtype=compact.dtype, device=compact.device)
+    if has_value is None:
+        has_value = torch.empty(N, dtype=torch.uint8, device=compact.device)
+    row_elems = 1
+    for s in row_shape:
+        row_elems *= s
+    row_bytes = row_elems * compact.element_size()
+    _check(lib.fsr_prune_restore(_ptr(compact, name="compact"), _ptr(dst_row, torch.int32, "dst_row"),
+                                 _ptr(restored, name="restored"), _ptr(has_value, torch.uint8, "has_value"),
+                                 ctypes.c_size_t(row_bytes), ctypes.c_int32(N), ctypes.c_uint32(pad_word), _stream()))
+    return restored, has_value
+
+
+def prune_scatter(compact, src_row, n_rows, out):
+    """fsr_prune_scatter: out[src_row[r]] = compact[r] for r < n_rows[0]."""
+    N_cap = src_row.shape[0]
+    if compact.shape[0] != N_cap or out.shape != compact.shape or out.dtype != compact.dtype:
+        raise ValueError("compact and out must be [N_cap, ...] of the same shape and dtype")
+    row_bytes = (compact.numel() // max(N_cap, 1)) * compact.element_size()
+    _check(load_library().fsr_prune_scatter(_ptr(compact, name="compact"), _ptr(src_row, torch.int32, "src_row"),
+                                            _ptr(n_rows, torch.int32, "n_rows"), _ptr(out, name="out"),
+                                            ctypes.c_size_t(row_bytes), ctypes.c_int32(N_cap), _stream()))
+    return out
+
+
+def frontier_init(spec_lens, pos, active, n_out, acc_total, out_tokens):
+    B = spec_lens.shape[0]
+    _check(load_library().fsr_frontier_init(
+        _ptr(spec_lens, torch.int32), _ptr(pos, torch.int32), _ptr(active, torch.int32), _ptr(n_out, torch.int32),
+        _ptr(acc_total, torch.int32), _ptr(out_tokens, torch.int32), ctypes.c_int32(B),
+        ctypes.c_int32(out_tokens.shape[1]), _stream()))
+
+
+def frontier_plan(ctx_lens, spec_lens, cu_q, cu_d, pos, active, chunk_len, t_mask, d_mask, chunk_ctx):
+    B = spec_lens.shape[0]
+    _check(load_library().fsr_frontier_plan(
+        _ptr(ctx_lens, torch.int32), _ptr(spec_lens, torch.int32), _ptr(cu_q, torch.int32), _ptr(cu_d, torch.int32),
+        _ptr(pos, torch.int32), _ptr(active, torch.int32), _ptr(chunk_len, torch.int32), _ptr(t_mask, torch.uint8),
+        _ptr(d_mask, torch.uint8), _ptr(chunk_ctx, torch.int32), ctypes.c_int32(B), ctypes.c_int32(t_mask.shape[0]),
+        ctypes.c_int32(d_mask.shape[0]), _stream()))
+
+
+def frontier_commit(spec_lens, chunk_len, accepted_len, n_emitted, emitted, pos, active, n_out, acc_total, out_tokens):
+    B = spec_lens.shape[0]
+    _check(load_library().fsr_frontier_commit(
+        _ptr(spec_lens, torch.int32), _ptr(chunk_len, torch.int32), _ptr(accepted_len, torch.int32),
+        _ptr(n_emitted, torch.int32), _ptr(emitted, torch.int32), ctypes.c_int32(emitted.shape[1]),
+        _ptr(pos, torch.int32), _ptr(active, torch.int32), _ptr(n_out, torch.int32), _ptr(acc_total, torch.int32),
+        _ptr(out_tokens, torch.int32), ctypes.c_int32(B), ctypes.c_int32(out_tokens.shape[1]), _stream()))

@@ -1,0 +1,12 @@
+// Library-wide entry points: last-error text and version.
+#include "common.hpp"
+
+namespace fsr {
+char* error_buffer() {
+    static thread_local char buf[256] = {0};
+    return buf;
+}
+}  // namespace fsr
+
+extern "C" const char* fsr_last_error(void) { return fsr::error_buffer(); }
+extern "C" const char* fsr_version(void) { return "faser_verify 0.1 (gfx950)"; }

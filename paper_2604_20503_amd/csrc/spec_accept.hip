@@ -1,0 +1,489 @@
+// spec_accept: accept / reject of drafted tokens with recovery or bonus token.
+//
+// Rule (Sec. 2.1 of the paper; the mismatch test and resampling distribution are those of
+// speculative sampling): accept drafts while u * q(x) < p(x); at the first rejection draw
+// one token from the normalised positive part of p - q; if everything is accepted and the
+// call carries the extra target row, draw the bonus token from it.
+//
+// Work split.  A verification batch has few requests (16 .. 512) but a vocabulary of
+// ~1.3e5, so one workgroup per request cannot fill the chip: every vocabulary row is cut
+// into chunks of kChunk tokens and the vocabulary-wide sums are two-level.
+//   stats    (LOGITS mode only) per (row, chunk): max and sum of exp in fp64
+//   decide   per request, one wave: the sequential accept tests (gathers only), picks the
+//            row pair to sample from and records it
+//   partials per (request, chunk): fp64 mass of the residual and of the target row
+//   select   per request: prefix over the chunk masses -> chunk holding u * R -> scan
+//            inside that chunk -> token
+// Only the rows the outcome needs are streamed: one target row (bonus) or one target and
+// one draft row (rejection) per request -- the algorithmic minimum in PROBS mode.
+// All masses are accumulated in fp64 so that the chosen token matches a sequential fp64
+// scan except when u * R lies within rounding of a CDF step.
+#include <climits>
+
+#include "common.hpp"
+#include "device_utils.hpp"
+
+namespace fsr {
+namespace {
+
+constexpr int kChunk = 4096;        // vocabulary tokens per chunk
+constexpr int kThreads = 256;       // threads per block in stats / partials / select
+constexpr int kPerThread = kChunk / kThreads;  // 16 contiguous tokens per thread in select
+
+enum : int { kCaseNone = 0, kCaseResidual = 1, kCaseTarget = 2 };
+
+// What `decide` hands to the later kernels, one per request.
+struct Decision {
+    long long t_row;  // storage row of the target distribution to sample from
+    long long d_row;  // storage row of the draft distribution (residual case)
+    double m_t, Z_t;  // LOGITS mode: max and partition sum of the target row
+    double m_d, Z_d;  // ... of the draft row
+    int kind;         // kCase*
+    int n;            // accepted drafts
+};
+
+struct Workspace {
+    Decision* dec;       // [B]
+    double* mass_res;    // [B, n_chunks]
+    double* mass_tgt;    // [B, n_chunks]
+    double* stat_t;      // [R_t_cap, n_chunks, 2]  (LOGITS)
+    double* stat_d;      // [R_d_cap, n_chunks, 2]
+};
+
+__host__ __device__ inline int n_chunks_of(int V) { return (V + kChunk - 1) / kChunk; }
+
+size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
+    const size_t nc = (size_t)n_chunks_of(p.V), B = (size_t)p.B;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* ptr = base ? base + off : nullptr;
+        off += align_up(bytes, 256);
+        return ptr;
+    };
+    Workspace tmp;
+    tmp.dec = (Decision*)take(B * sizeof(Decision));
+    tmp.mass_res = (double*)take(B * nc * sizeof(double));
+    tmp.mass_tgt = (double*)take(B * nc * sizeof(double));
+    if (p.mode == FSR_LOGITS) {
+        tmp.stat_t = (double*)take(B * (size_t)(p.S_max + 1) * nc * 2 * sizeof(double));
+        tmp.stat_d = (double*)take(B * (size_t)p.S_max * nc * 2 * sizeof(double));
+    } else {
+        tmp.stat_t = tmp.stat_d = nullptr;
+    }
+    if (w) *w = tmp;
+    return off;
+}
+
+__device__ __forceinline__ double block_sum(double v, double* smem) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) smem[w] = v;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int k = 0; k < kThreads / 64; ++k) t += smem[k];
+    return t;
+}
+
+// Four consecutive values of a row starting at token e (bounds-checked; vector load when
+// the row is 16-byte aligned).
+__device__ __forceinline__ void load_quad(const float* __restrict__ row, int e, int V, bool vec, float (&x)[4]) {
+    if (vec && e + 3 < V) {
+        const float4 t = *reinterpret_cast<const float4*>(row + e);
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? row[e + k] : 0.0f;
+    }
+}
+
+// Probability of one entry in fp64: the value itself, or exp(z / T - m) / Z.
+template <int MODE>
+__device__ __forceinline__ double prob_of(float x, double T, double m, double Z) {
+    if constexpr (MODE == FSR_PROBS) {
+        return (double)x;
+    } else {
+        return exp((double)x / T - m) / Z;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// LOGITS mode: per (row, chunk) max of z/T and sum of exp(z/T - max), fp64.
+// grid = (n_chunks, R_t_cap + R_d_cap)
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void accept_stats_kernel(
+    const float* __restrict__ z_target, const float* __restrict__ z_draft, const int32_t* __restrict__ cu_t,
+    const int32_t* __restrict__ cu_d, const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows,
+    Workspace ws, int B, int V, int R_t_cap, double T) {
+    __shared__ double smem[kThreads / 64];
+    __shared__ float smax[kThreads / 64];
+    const int c = blockIdx.x, nc = gridDim.x;
+    int r = blockIdx.y;
+    const float* rows;
+    double* stat;
+    if (r < R_t_cap) {
+        if (r >= cu_t[B]) return;
+        rows = z_target + (size_t)(t_rows ? t_rows[r] : r) * V;
+        stat = ws.stat_t + ((size_t)r * nc + c) * 2;
+    } else {
+        r -= R_t_cap;
+        if (r >= cu_d[B]) return;
+        rows = z_draft + (size_t)(d_rows ? d_rows[r] : r) * V;
+        stat = ws.stat_d + ((size_t)r * nc + c) * 2;
+    }
+    const bool vec = ((uintptr_t)rows & 15) == 0;
+    const int e0 = c * kChunk;
+    float vals[kPerThread];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kPerThread / 4; ++k) {
+        const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+        float x[4];
+        load_quad(rows, e, V, vec, x);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            vals[k * 4 + j] = (e + j < V) ? x[j] : -INFINITY;
+            mx = fmaxf(mx, vals[k * 4 + j]);
+        }
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(smax[0], smax[1]), fmaxf(smax[2], smax[3]));
+    const double m = (double)mx / T;  // max of z/T (T > 0): division is monotone
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k)
+        if (vals[k] != -INFINITY) s += exp((double)vals[k] / T - m);
+    s = block_sum(s, smem);
+    if (threadIdx.x == 0) {
+        stat[0] = m;
+        stat[1] = s;
+    }
+}
+
+// Combine a row's chunk statistics into (max, partition sum); all lanes of the wave call it.
+__device__ __forceinline__ void combine_stats(const double* __restrict__ stat, int nc, double& m, double& Z) {
+    const int lane = threadIdx.x & 63;
+    double mm = -INFINITY;
+    for (int c = lane; c < nc; c += 64) mm = fmax(mm, stat[c * 2]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mm = fmax(mm, __shfl_xor(mm, o, 64));
+    double z = 0.0;
+    for (int c = lane; c < nc; c += 64) z += stat[c * 2 + 1] * exp(stat[c * 2] - mm);
+    m = mm;
+    Z = wave_sum(z);
+}
+
+// ---------------------------------------------------------------------------------------
+// decide: one wave per request runs the accept tests in order.
+// ---------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(64) void accept_decide_kernel(
+    const float* __restrict__ p_target, const float* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
+    const float* __restrict__ u_accept, const int32_t* __restrict__ cu_t, const int32_t* __restrict__ cu_d,
+    const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows, int32_t* __restrict__ accepted_len,
+    int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int nc = n_chunks_of(V);
+    const int t0 = cu_t[i], t_i = cu_t[i + 1] - t0, d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
+    int32_t* em = emitted + (size_t)i * (S_max + 1);
+    Decision dec;
+    dec.kind = kCaseNone;
+    dec.n = 0;
+    dec.t_row = dec.d_row = 0;
+    dec.m_t = dec.m_d = 0.0;
+    dec.Z_t = dec.Z_d = 1.0;
+    // the per-row statistics hold B*(S_max+1) target and B*S_max draft rows: a call whose offsets
+    // run past that (only possible after an invalid request) is refused for the requests beyond
+    const bool fits = (long long)t0 + t_i <= (long long)B * (S_max + 1) && (long long)d0 + d_i <= (long long)B * S_max;
+    if (d_i < 0 || d_i > S_max || t_i < d_i || t_i > d_i + 1 || t0 < 0 || d0 < 0 || !fits) {
+        for (int s = lane; s <= S_max; s += 64) em[s] = -1;
+        if (lane == 0) {
+            accepted_len[i] = -1;
+            n_emitted[i] = -1;
+            ws.dec[i] = dec;
+        }
+        return;
+    }
+    int n = 0;
+    double m_t = 0.0, Z_t = 1.0, m_d = 0.0, Z_d = 1.0;
+    long long tr = 0, dr = 0;
+    while (n < d_i) {
+        tr = t_rows ? t_rows[t0 + n] : t0 + n;
+        dr = d_rows ? d_rows[d0 + n] : d0 + n;
+        const int x = min(max(draft_tokens[dr], 0), V - 1);
+        const double u = (double)u_accept[dr];
+        if constexpr (MODE == FSR_LOGITS) {
+            combine_stats(ws.stat_t + (size_t)(t0 + n) * nc * 2, nc, m_t, Z_t);
+            combine_stats(ws.stat_d + (size_t)(d0 + n) * nc * 2, nc, m_d, Z_d);
+        }
+        const double px = prob_of<MODE>(p_target[(size_t)tr * V + x], T, m_t, Z_t);
+        const double qx = prob_of<MODE>(p_draft[(size_t)dr * V + x], T, m_d, Z_d);
+        if (u * qx < px) {
+            if (lane == 0) em[n] = x;
+            ++n;
+        } else {
+            break;
+        }
+    }
+    dec.n = n;
+    if (n < d_i) {
+        dec.kind = kCaseResidual;
+        dec.t_row = tr;
+        dec.d_row = dr;
+        dec.m_t = m_t; dec.Z_t = Z_t; dec.m_d = m_d; dec.Z_d = Z_d;
+    } else if (t_i == d_i + 1) {
+        dec.kind = kCaseTarget;
+        dec.t_row = t_rows ? t_rows[t0 + d_i] : t0 + d_i;
+        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nc * 2, nc, dec.m_t, dec.Z_t);
+    }
+    for (int s = n + lane; s <= S_max; s += 64) em[s] = -1;
+    if (lane == 0) {
+        accepted_len[i] = n;
+        n_emitted[i] = n;  // select adds the sampled token
+        ws.dec[i] = dec;
+    }
+}
+
+// Masses of 4 consecutive tokens starting at e for the request's decision.
+template <int MODE>
+__device__ __forceinline__ void quad_masses(const Decision& dec, const float* __restrict__ trow,
+                                            const float* __restrict__ drow, int e, int V, bool vec_t, bool vec_d,
+                                            double T, double (&res)[4], double (&tgt)[4]) {
+    float a[4], b[4];
+    load_quad(trow, e, V, vec_t, a);
+    if (dec.kind == kCaseResidual) load_quad(drow, e, V, vec_d, b);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const bool ok = e + k < V;
+        const double pt = ok ? prob_of<MODE>(a[k], T, dec.m_t, dec.Z_t) : 0.0;
+        tgt[k] = pt;
+        if (dec.kind == kCaseResidual) {
+            const double qd = ok ? prob_of<MODE>(b[k], T, dec.m_d, dec.Z_d) : 0.0;
+            const double r = pt - qd;
+            res[k] = r > 0.0 ? r : 0.0;
+        } else {
+            res[k] = pt;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// partials: fp64 mass of chunk c of request i's sampling distribution.  grid = (n_chunks, B)
+// ---------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void accept_partials_kernel(const float* __restrict__ p_target,
+                                                                  const float* __restrict__ p_draft, Workspace ws,
+                                                                  int V, double T) {
+    __shared__ double smem[kThreads / 64];
+    const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
+    const Decision dec = ws.dec[i];
+    if (dec.kind == kCaseNone) return;
+    const float* trow = p_target + (size_t)dec.t_row * V;
+    const float* drow = p_draft + (size_t)dec.d_row * V;
+    const bool vec_t = ((uintptr_t)trow & 15) == 0, vec_d = ((uintptr_t)drow & 15) == 0;
+    const int e0 = c * kChunk;
+    double sr = 0.0, st = 0.0;
+#pragma unroll
+    for (int k = 0; k < kPerThread / 4; ++k) {
+        const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+        double res[4], tgt[4];
+        quad_masses<MODE>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
+        sr += (res[0] + res[1]) + (res[2] + res[3]);
+        st += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+    }
+    sr = block_sum(sr, smem);
+    st = block_sum(st, smem);
+    if (threadIdx.x == 0) {
+        ws.mass_res[(size_t)i * nc + c] = sr;
+        ws.mass_tgt[(size_t)i * nc + c] = st;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// select: inverse CDF.  grid = (B)
+// ---------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void accept_select_kernel(const float* __restrict__ p_target,
+                                                                const float* __restrict__ p_draft,
+                                                                const float* __restrict__ u_sample,
+                                                                int32_t* __restrict__ n_emitted,
+                                                                int32_t* __restrict__ emitted, Workspace ws, int V,
+                                                                int S_max, double T) {
+    __shared__ double s_wave[kThreads / 64];
+    __shared__ int s_i[kThreads / 64];
+    __shared__ double s_base, s_thr;
+    __shared__ int s_chunk, s_fallback;
+    const int i = blockIdx.x, nc = n_chunks_of(V);
+    Decision dec = ws.dec[i];
+    if (dec.kind == kCaseNone) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+
+    // 1. total mass and the chunk that holds u * R (sequential fp64 prefix over <= a few dozen chunks)
+    if (threadIdx.x == 0) {
+        const double* mres = ws.mass_res + (size_t)i * nc;
+        const double* mtgt = ws.mass_tgt + (size_t)i * nc;
+        double R = 0.0;
+        for (int c = 0; c < nc; ++c) R += mres[c];
+        int fallback = 0;
+        const double* mass = mres;
+        if (!(R > 0.0)) {  // residual is all zero: sample from the target row itself
+            fallback = 1;
+            mass = mtgt;
+            R = 0.0;
+            for (int c = 0; c < nc; ++c) R += mtgt[c];
+        }
+        const double thr = (double)u_sample[i] * R;
+        double acc = 0.0, base = 0.0;
+        int chunk = -1, last_pos = 0;
+        double last_base = 0.0;
+        for (int c = 0; c < nc; ++c) {
+            const double prev = acc;
+            acc += mass[c];
+            if (mass[c] > 0.0) {
+                last_pos = c;
+                last_base = prev;
+                if (acc > thr) {
+                    chunk = c;
+                    base = prev;
+                    break;
+                }
+            }
+        }
+        if (chunk < 0) {  // rounding left no chunk: the last chunk with mass
+            chunk = last_pos;
+            base = last_base;
+        }
+        s_base = base;
+        s_thr = thr;
+        s_chunk = chunk;
+        s_fallback = fallback;
+    }
+    __syncthreads();
+    if (s_fallback) dec.kind = kCaseTarget;
+    const double thr = s_thr;
+    const int c = s_chunk;
+
+    // 2. scan inside the chunk: thread t owns tokens [16 t, 16 t + 16) of the chunk
+    const float* trow = p_target + (size_t)dec.t_row * V;
+    const float* drow = p_draft + (size_t)dec.d_row * V;
+    const bool vec_t = ((uintptr_t)trow & 15) == 0, vec_d = ((uintptr_t)drow & 15) == 0;
+    const int e0 = c * kChunk + threadIdx.x * kPerThread;
+    double mass[kPerThread];
+    double local = 0.0;
+#pragma unroll
+    for (int k = 0; k < kPerThread / 4; ++k) {
+        double res[4], tgt[4];
+        quad_masses<MODE>(dec, trow, drow, e0 + 4 * k, V, vec_t, vec_d, T, res, tgt);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            mass[4 * k + j] = res[j];
+            local += res[j];
+        }
+    }
+    const double inc = wave_inclusive_scan(local);
+    if (lane == 63) s_wave[w] = inc;
+    __syncthreads();
+    double run = s_base + (inc - local);
+    for (int k = 0; k < w; ++k) run += s_wave[k];
+    int hit = INT_MAX, last_pos = -1;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        run += mass[k];
+        if (mass[k] > 0.0) {
+            last_pos = e0 + k;
+            if (run > thr && hit == INT_MAX) hit = e0 + k;
+        }
+    }
+    hit = wave_min_i(hit);
+    last_pos = wave_max_i(last_pos);
+    __syncthreads();
+    if (lane == 0) s_i[w] = hit;
+    __syncthreads();
+    hit = min(min(s_i[0], s_i[1]), min(s_i[2], s_i[3]));
+    __syncthreads();
+    if (lane == 0) s_i[w] = last_pos;
+    __syncthreads();
+    last_pos = max(max(s_i[0], s_i[1]), max(s_i[2], s_i[3]));
+    if (threadIdx.x == 0) {
+        int tok = hit != INT_MAX ? hit : last_pos;
+        if (tok < 0) tok = 0;  // unreachable for a chunk with mass; keeps the id in range
+        emitted[(size_t)i * (S_max + 1) + dec.n] = tok;
+        n_emitted[i] = dec.n + 1;
+    }
+}
+
+template <int MODE>
+int launch_all(const float* p_target, const float* p_draft, const int32_t* draft_tokens, const float* u_accept,
+               const float* u_sample, const int32_t* cu_t, const int32_t* cu_d, const int32_t* t_rows,
+               const int32_t* d_rows, int32_t* accepted_len, int32_t* n_emitted, int32_t* emitted,
+               const fsr_accept_params& p, const Workspace& ws, hipStream_t s) {
+    const int nc = n_chunks_of(p.V);
+    const double T = p.temperature;
+    int rc;
+    if (MODE == FSR_LOGITS) {
+        const int R_t_cap = p.B * (p.S_max + 1), R_d_cap = p.B * p.S_max;
+        hipLaunchKernelGGL(accept_stats_kernel, dim3(nc, R_t_cap + R_d_cap), dim3(kThreads), 0, s, p_target, p_draft, cu_t,
+                           cu_d, t_rows, d_rows, ws, p.B, p.V, R_t_cap, T);
+        if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
+    }
+    hipLaunchKernelGGL(accept_decide_kernel<MODE>, dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
+                       cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T);
+    if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
+    hipLaunchKernelGGL(accept_partials_kernel<MODE>, dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, ws, p.V, T);
+    if ((rc = check_launch("accept_partials_kernel")) != FSR_OK) return rc;
+    hipLaunchKernelGGL(accept_select_kernel<MODE>, dim3(p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
+                       emitted, ws, p.V, p.S_max, T);
+    return check_launch("accept_select_kernel");
+}
+
+int validate(const fsr_accept_params* p, const char* who) {
+    if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
+    if (p->B < 0 || p->V <= 0 || p->S_max < 0 || p->reserved != 0 || p->reserved2 != 0)
+        return fail(FSR_EINVAL, "%s: B=%d V=%d S_max=%d reserved=%d", who, p->B, p->V, p->S_max, p->reserved);
+    if (p->mode != FSR_PROBS && p->mode != FSR_LOGITS) return fail(FSR_EUNSUP, "%s: mode=%d", who, p->mode);
+    if (p->mode == FSR_LOGITS && !(p->temperature > 0.0)) return fail(FSR_EINVAL, "%s: temperature=%g must be > 0", who, p->temperature);
+    if ((long long)p->B * (2LL * p->S_max + 1) > 65535) return fail(FSR_EUNSUP, "%s: B*(2*S_max+1)=%lld exceeds 65535 rows per call", who, (long long)p->B * (2LL * p->S_max + 1));
+    return FSR_OK;
+}
+
+}  // namespace
+}  // namespace fsr
+
+using namespace fsr;
+
+extern "C" int fsr_accept_workspace_bytes(const fsr_accept_params* p, size_t* out_bytes) {
+    int rc = validate(p, "fsr_accept_workspace_bytes");
+    if (rc != FSR_OK) return rc;
+    if (!out_bytes) return fail(FSR_EINVAL, "fsr_accept_workspace_bytes: out_bytes is null");
+    *out_bytes = carve(*p, nullptr, nullptr);
+    return FSR_OK;
+}
+
+extern "C" int fsr_spec_accept(const float* p_target, const float* p_draft, const int32_t* draft_tokens,
+                               const float* u_accept, const float* u_sample, const int32_t* cu_t, const int32_t* cu_d,
+                               const int32_t* t_rows, const int32_t* d_rows, int32_t* accepted_len, int32_t* n_emitted,
+                               int32_t* emitted, const fsr_accept_params* p, void* workspace, size_t ws_bytes,
+                               void* stream) {
+    int rc = validate(p, "fsr_spec_accept");
+    if (rc != FSR_OK) return rc;
+    if (p->B == 0) return FSR_OK;
+    if (!p_target || !u_sample || !cu_t || !cu_d || !accepted_len || !n_emitted || !emitted)
+        return fail(FSR_EINVAL, "fsr_spec_accept: null pointer among p_target/u_sample/cu_t/cu_d/outputs");
+    if (p->S_max > 0 && (!p_draft || !draft_tokens || !u_accept))
+        return fail(FSR_EINVAL, "fsr_spec_accept: p_draft/draft_tokens/u_accept is null with S_max=%d", p->S_max);
+    Workspace ws;
+    const size_t need = carve(*p, (char*)workspace, &ws);
+    if (!workspace || ws_bytes < need) return fail(FSR_EWS, "fsr_spec_accept: workspace %zu bytes, need %zu", ws_bytes, need);
+    if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "fsr_spec_accept: workspace must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    // a request without drafts never dereferences the draft arrays; give the kernels a valid base
+    if (!p_draft) p_draft = p_target;
+    if (p->mode == FSR_LOGITS)
+        return launch_all<FSR_LOGITS>(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows,
+                                      accepted_len, n_emitted, emitted, *p, ws, s);
+    return launch_all<FSR_PROBS>(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows,
+                                 accepted_len, n_emitted, emitted, *p, ws, s);
+}

@@ -1,0 +1,79 @@
+"""Helpers shared by the GPU parity tests: host batch -> device tensors, error metrics."""
+import sys
+
+import numpy as np
+import torch
+
+
+def announce(msg):
+    """Name the case before a GPU step so a fault can be traced to it."""
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def dev(x, bf16=False):
+    t = torch.from_numpy(np.ascontiguousarray(x if not bf16 else x.view(np.int16)))
+    t = t.cuda()
+    return t.view(torch.bfloat16) if bf16 else t
+
+
+class DeviceBatch:
+    def __init__(self, b, probs=True, kv=True, logits=False):
+        bf = b.dtype == "bf16"
+        self.b = b
+        self.ctx_lens, self.spec_lens = dev(b.ctx_lens), dev(b.spec_lens)
+        self.cu_q, self.cu_d = dev(b.cu_q), dev(b.cu_d)
+        self.block_tables = dev(b.block_tables)
+        if kv:
+            self.q, self.k_cache, self.v_cache = dev(b.q, bf), dev(b.k_cache, bf), dev(b.v_cache, bf)
+        if probs:
+            self.p_target, self.p_draft = dev(b.p_target), dev(b.p_draft)
+            self.draft_tokens, self.u_accept, self.u_sample = dev(b.draft_tokens), dev(b.u_accept), dev(b.u_sample)
+        if logits:
+            self.z_target, self.z_draft = dev(b.z_target), dev(b.z_draft)
+
+
+def attn_rel_err(o_gpu: np.ndarray, o_ref: np.ndarray):
+    """|o_gpu - o_ref| / max(|o_ref|, rms of the (row, head) vector), elementwise."""
+    rms = np.sqrt((o_ref ** 2).mean(axis=-1, keepdims=True))
+    return np.abs(o_gpu - o_ref) / np.maximum(np.abs(o_ref), rms)
+
+
+def check_attention(o_gpu_t: torch.Tensor, o_ref: np.ndarray, in_dtype: str, n_rows: int):
+    """Tolerance of the benchmark spec: 1e-5 relative for fp32 inputs, 2e-3 for bf16 inputs, measured
+    on the value before the output cast; a bf16 output adds its own rounding, at most half an ulp
+    (2^-8 relative)."""
+    o = o_gpu_t[:n_rows].float().cpu().numpy().astype(np.float64)
+    ref = o_ref[:n_rows]
+    assert np.isfinite(o).all()
+    tol = 1e-5 if in_dtype == "f32" else 2e-3
+    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    den = np.maximum(np.abs(ref), rms)
+    bound = tol * den
+    if o_gpu_t.dtype == torch.bfloat16:
+        bound = bound + 2.0 ** -8 * np.abs(ref)
+    bad = np.abs(o - ref) > bound
+    err = (np.abs(o - ref) / den).max() if o.size else 0.0
+    assert not bad.any(), f"{bad.sum()} of {bad.size} elements out of tolerance; max rel err {err:.3e}"
+    return err
+
+
+def fragile_draws(u_sample, cdf_lo, cdf_hi, band=1e-6):
+    """Requests whose uniform lies within `band` of an edge of the oracle token's CDF interval."""
+    u = u_sample.astype(np.float64)
+    with np.errstate(invalid="ignore"):
+        return (np.abs(u - cdf_lo) < band) | (np.abs(u - cdf_hi) < band)
+
+
+def check_accept(gpu, ref, u_sample):
+    """accepted_len / n_emitted bit-exact; emitted bit-exact except fragile draws (counted)."""
+    acc, nem, em = (t.cpu().numpy() for t in gpu)
+    assert np.array_equal(acc, ref["accepted_len"])
+    assert np.array_equal(nem, ref["n_emitted"])
+    frag = fragile_draws(u_sample, ref["cdf_lo"], ref["cdf_hi"])
+    diff_rows = np.where((em != ref["emitted"]).any(axis=1))[0]
+    for i in diff_rows:
+        assert frag[i], f"request {i}: emitted {em[i]} vs oracle {ref['emitted'][i]} and the draw is not fragile"
+        n = ref["accepted_len"][i]
+        assert np.array_equal(em[i, :n], ref["emitted"][i, :n])
+    return int(frag.sum()), len(diff_rows)

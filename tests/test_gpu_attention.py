@@ -1,0 +1,130 @@
+"""GPU parity: verify_attention vs the oracle, element by element.
+Tolerance (the benchmark spec): 1e-5 relative for fp32 inputs, 2e-3 for bf16 inputs, relative to
+max(|o_ref|, rms of the (row, head) vector)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_utils import DeviceBatch, announce, check_attention, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fsr():
+    import paper_2604_20503_amd as f
+    f.load_library()
+    return f
+
+
+def ref_of(oracle, b, **kw):
+    return oracle.verify_attention(kw.get("q", b.q), kw.get("k", b.k_cache), kw.get("v", b.v_cache), b.block_tables,
+                                   kw.get("ctx", b.ctx_lens), kw.get("cu", b.cu_q), H_q=b.H_q, H_kv=b.H_kv, D=b.D,
+                                   P=b.P, dtype=b.dtype, scale=b.scale)
+
+
+def run_gpu(fsr, b, d, out_dtype, max_q_len=None, want_lse=True):
+    lse = torch.zeros((b.N, b.H_q), dtype=torch.float32, device="cuda") if want_lse else None
+    mq = b.S_max + 1 if max_q_len is None else max_q_len
+    out, lse = fsr.verify_attention(d.q, d.k_cache, d.v_cache, d.block_tables, d.ctx_lens, d.spec_lens, d.cu_q,
+                                    scale=b.scale, out_dtype=out_dtype, lse=lse, max_q_len=mq)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def test_config1_fp32(fsr, oracle):
+    announce("attention config1 fp32 (generic path)")
+    b = workloads.make_batch(1, with_probs=False)
+    d = DeviceBatch(b, probs=False)
+    o_ref, lse_ref = ref_of(oracle, b)
+    out, lse = run_gpu(fsr, b, d, torch.float32)
+    err = check_attention(out, o_ref, "f32", b.N)
+    print(f"config1 fp32 max rel err {err:.3e}")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("heads", [(32, 8), (8, 8), (16, 8), (64, 8), (16, 1)])
+def test_bf16_fast_path_small(fsr, oracle, heads, out_dtype):
+    H_q, H_kv = heads
+    announce(f"attention bf16 fast small heads={heads} out={out_dtype}")
+    ctx = [0, 1, 15, 16, 31, 33, 100, 257, 511, 640, 700, 1029]
+    spec = [3, 0, 8, 1, 2, 7, 4, 10, 5, 6, 0, 9]
+    b = workloads.make_batch(2, rep=H_q, with_probs=False, H_q=H_q, H_kv=H_kv, ctx_lens=ctx, spec_lens=spec)
+    d = DeviceBatch(b, probs=False)
+    o_ref, lse_ref = ref_of(oracle, b)
+    out, lse = run_gpu(fsr, b, d, out_dtype)
+    err = check_attention(out, o_ref, "bf16", b.N)
+    print(f"heads={heads} out={out_dtype} max rel err {err:.3e}")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
+
+
+@pytest.mark.parametrize("max_q_len", [0, 1, 2, 5])
+def test_bf16_row_bound_hint_only_changes_speed(fsr, oracle, max_q_len):
+    announce(f"attention bf16 max_q_len hint={max_q_len}")
+    b = workloads.make_batch(2, rep=77, with_probs=False, ctx_lens=[300, 45, 513, 128], spec_lens=[8, 3, 6, 0])
+    d = DeviceBatch(b, probs=False)
+    o_ref, _ = ref_of(oracle, b)
+    out, _ = run_gpu(fsr, b, d, torch.float32, max_q_len=max_q_len, want_lse=False)
+    check_attention(out, o_ref, "bf16", b.N)
+
+
+def test_bf16_garbage_beyond_length_is_ignored(fsr, oracle):
+    """Slots past a request's last token (page tails, spare pages) hold NaN: the output must not change."""
+    announce("attention bf16 NaN poison beyond kv length")
+    b = workloads.make_batch(2, rep=5, with_probs=False, ctx_lens=[37, 200, 16, 95], spec_lens=[2, 5, 0, 7])
+    o_ref, _ = ref_of(oracle, b)
+    used = np.zeros((b.n_pages, b.P), bool)
+    for i in range(b.B):
+        L = int(b.ctx_lens[i] + b.spec_lens[i] + 1)
+        for t in range(L):
+            used[b.block_tables[i, t // b.P], t % b.P] = True
+    nan16 = np.uint16(0x7FC0)
+    d = DeviceBatch(b, probs=False)
+    kk = np.ascontiguousarray(np.moveaxis(b.k_cache, 1, 2)).copy()
+    vv = np.ascontiguousarray(np.moveaxis(b.v_cache, 1, 2)).copy()
+    kk[~used] = nan16
+    vv[~used] = nan16
+    d.k_cache = dev(np.ascontiguousarray(np.moveaxis(kk, 2, 1)), True)
+    d.v_cache = dev(np.ascontiguousarray(np.moveaxis(vv, 2, 1)), True)
+    out, _ = run_gpu(fsr, b, d, torch.float32, want_lse=False)
+    check_attention(out, o_ref, "bf16", b.N)
+
+
+def test_empty_request_and_row_capacity(fsr, oracle):
+    announce("attention empty request, N_cap > N")
+    b = workloads.make_batch(2, rep=6, with_probs=False, ctx_lens=[120, 64, 300], spec_lens=[2, 4, 1])
+    # re-deal the rows: request 1 gets none
+    cu = np.array([0, 3, 3, 5], np.int32)
+    o_ref, _ = ref_of(oracle, b, q=b.q[:5], cu=cu)
+    d = DeviceBatch(b, probs=False)
+    out, _ = fsr.verify_attention(d.q, d.k_cache, d.v_cache, d.block_tables, d.ctx_lens, None, dev(cu), scale=b.scale,
+                                  out_dtype=torch.float32, max_q_len=3)
+    torch.cuda.synchronize()
+    check_attention(out, o_ref, "bf16", 5)
+
+
+def test_generic_bf16_d64(fsr, oracle):
+    announce("attention bf16 D=64 (generic path)")
+    b = workloads.make_batch(1, rep=2, with_probs=False, dtype="bf16")
+    d = DeviceBatch(b, probs=False)
+    o_ref, _ = ref_of(oracle, b)
+    for od in (torch.float32, torch.bfloat16):
+        out, _ = run_gpu(fsr, b, d, od, want_lse=False)
+        check_attention(out, o_ref, "bf16", b.N)
+
+
+def test_config2_full_size_and_determinism(fsr, oracle):
+    announce("attention config2 full size")
+    b = workloads.make_batch(2, with_probs=False)
+    d = DeviceBatch(b, probs=False)
+    o_ref, lse_ref = ref_of(oracle, b)
+    out, lse = run_gpu(fsr, b, d, torch.bfloat16)
+    err = check_attention(out, o_ref, "bf16", b.N)
+    out32, _ = run_gpu(fsr, b, d, torch.float32, want_lse=False)
+    err32 = check_attention(out32, o_ref, "bf16", b.N)
+    print(f"config2: max rel err bf16-out {err:.3e}, fp32-out {err32:.3e}")
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
+    out2, _ = run_gpu(fsr, b, d, torch.bfloat16, want_lse=False)
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))  # same bits on a re-run
