@@ -199,6 +199,15 @@ int fsr_prune_restore(const void* compact, const int32_t* dst_row, void* restore
                       void* stream);
 
 /*
+ * Keep mask after a one-shot accept step (Sec. 2.1: the rejected suffix is discarded): row j of
+ * request i is kept iff j <= accepted_len[i], i.e. the rows of the last committed token and of the
+ * accepted drafts survive, the rows of rejected drafts do not.  keep_mask [N_cap] uint8 in the
+ * cu_q layout; rows >= cu_q[B] are not written.  Feed it to fsr_prune_compact.
+ */
+int fsr_survivor_mask(const int32_t* accepted_len, const int32_t* cu_q, uint8_t* keep_mask, int32_t B,
+                      int32_t N_cap, void* stream);
+
+/*
  * Partial restore (Sec. 3.2, same passage): out[src_row[r]] = compact[r] for r < n_rows[0];
  * rows of `out` that no compacted row maps to keep their contents.  Used to put one chunk's
  * rows back into the original layout while other chunks' rows stay.  src_row [N_cap] and

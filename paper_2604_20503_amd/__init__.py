@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     prune_restore,
     prune_scatter,
     spec_accept,
+    survivor_mask,
     verify_attention,
     version,
 )
@@ -27,5 +28,5 @@ from .frontier import verify_chunked  # noqa: F401
 __all__ = [
     "FsrError", "accept_workspace_bytes", "attn_workspace_bytes", "frontier_commit", "frontier_init",
     "frontier_plan", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
-    "spec_accept", "verify_attention", "verify_chunked", "version",
+    "spec_accept", "survivor_mask", "verify_attention", "verify_chunked", "version",
 ]

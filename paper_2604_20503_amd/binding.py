@@ -22,7 +22,7 @@ PROBS, LOGITS = 0, 1
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
-    "fsr_prune_scatter", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
+    "fsr_prune_scatter", "fsr_survivor_mask", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
 
 
@@ -260,6 +260,15 @@ def prune_scatter(compact, src_row, n_rows, out):
                                             _ptr(n_rows, torch.int32, "n_rows"), _ptr(out, name="out"),
                                             ctypes.c_size_t(row_bytes), ctypes.c_int32(N_cap), _stream()))
     return out
+
+
+def survivor_mask(accepted_len, cu_q, keep_mask):
+    """fsr_survivor_mask: keep rows 0..accepted_len[i] of every request."""
+    B = accepted_len.shape[0]
+    _check(load_library().fsr_survivor_mask(_ptr(accepted_len, torch.int32, "accepted_len"), _ptr(cu_q, torch.int32, "cu_q"),
+                                            _ptr(keep_mask, torch.uint8, "keep_mask"), ctypes.c_int32(B),
+                                            ctypes.c_int32(keep_mask.shape[0]), _stream()))
+    return keep_mask
 
 
 def frontier_init(spec_lens, pos, active, n_out, acc_total, out_tokens):

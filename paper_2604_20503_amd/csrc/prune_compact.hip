@@ -140,6 +140,17 @@ __global__ __launch_bounds__(256) void restore_rows_kernel(const VecT* __restric
     }
 }
 
+// keep[r] = 1 for rows 0 .. accepted_len[i] of request i (the rows whose tokens stay committed after
+// the accept step: the last committed token and the accepted drafts), 0 for the rejected suffix.
+__global__ void survivor_mask_kernel(const int32_t* __restrict__ accepted_len, const int32_t* __restrict__ cu_q,
+                                     uint8_t* __restrict__ keep, int B, int N_cap) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    const int r0 = min(max(cu_q[i], 0), N_cap), r1 = min(max(cu_q[i + 1], r0), N_cap);
+    const int n = accepted_len[i];
+    for (int r = r0; r < r1; ++r) keep[r] = (r - r0 <= n) ? 1 : 0;
+}
+
 __global__ void frontier_init_kernel(const int32_t* __restrict__ spec_lens, int32_t* pos, int32_t* active,
                                      int32_t* n_out, int32_t* acc_total, int32_t* out_tokens, int B, int out_stride) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -274,6 +285,16 @@ extern "C" int fsr_prune_scatter(const void* compact, const int32_t* src_row, co
                            src_row, n_rows, row_vecs, N_cap);
         return check_launch("scatter_rows_kernel");
     });
+}
+
+extern "C" int fsr_survivor_mask(const int32_t* accepted_len, const int32_t* cu_q, uint8_t* keep_mask, int32_t B,
+                                 int32_t N_cap, void* stream) {
+    if (B < 0 || N_cap < 0) return fail(FSR_EINVAL, "fsr_survivor_mask: B=%d N_cap=%d", B, N_cap);
+    if (B == 0 || N_cap == 0) return FSR_OK;
+    if (!accepted_len || !cu_q || !keep_mask) return fail(FSR_EINVAL, "fsr_survivor_mask: null pointer");
+    hipLaunchKernelGGL(survivor_mask_kernel, dim3((B + 255) / 256), dim3(256), 0, (hipStream_t)stream, accepted_len, cu_q,
+                       keep_mask, B, N_cap);
+    return check_launch("survivor_mask_kernel");
 }
 
 extern "C" int fsr_frontier_init(const int32_t* spec_lens, int32_t* pos, int32_t* active, int32_t* n_out,
