@@ -22,10 +22,12 @@
 //   * P is fed to the matrix cores as a bf16 hi + lo pair: the result is accurate to fp32
 //     rounding instead of bf16 rounding of the probabilities;
 //   * an item that lies inside one share is normalised and written directly; an item cut by
-//     a share boundary leaves (max, sum, accumulator) partials -- at most two per workgroup --
-//     that a small fix-up kernel combines.
+//     a share boundary leaves (reference, sum, accumulator) partials -- at most two per workgroup
+//     -- and the workgroup whose piece arrives last combines them, in the same launch.
 // Generic path (fp32 or bf16, D in {64,128}, any page size): one wave per (row, head), plain
 // fp32 FMAs -- a correctness path for small or unusual shapes, not a bandwidth kernel.
+#include <atomic>
+
 #include "common.hpp"
 #include "device_utils.hpp"
 
@@ -58,8 +60,10 @@ constexpr int kMlBytes = 2 * kWaves * 16 * kMaxMT * 4;
 constexpr int kQOff = kMlOff + kMlBytes;          // Q^T operands of the current item: [kMaxMT * 4][64 lanes][16 B]
 constexpr int kQBytes = kMaxMT * 4 * 64 * 16;
 constexpr int kPrefOff = kQOff + kQBytes;
-constexpr int kPrefBytes = (kMaxB + 1) * 4;
-constexpr int kScanOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
+constexpr int kPrefBytes = (kMaxB + 1) * 8;          // weighted tile prefix (64-bit)
+constexpr int kCostOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
+constexpr int kCostBytes = ((kMaxB + 15) / 16) * 16;  // per-request cost of one tile (bytes)
+constexpr int kScanOff = kCostOff + kCostBytes;
 constexpr int kFastSmem = kScanOff + 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -74,7 +78,9 @@ struct FastArgs {
     void* out;       // [N_cap, H_q, D] bf16 or fp32
     float* lse;      // nullable
     float* part_o;   // [nb * 2, m_cap, D]   unnormalised accumulators of cut items
-    float* part_ml;  // [nb * 2, m_cap, 2]   (max in log2 units, sum)
+    float* part_ml;  // [nb * 2, m_cap, 2]   (exponent reference in log2 units, sum)
+    unsigned long long* arrivals;  // [nb] (call id << 16 | pieces of a cut item that have arrived)
+    unsigned long long call_id;    // distinguishes this call's counts from whatever the words held before
     int B, H_q, H_kv, G, max_pages, n_pages;
     int nb;          // workgroups of the persistent grid
     int m_cap;       // rows (G * q_len) a partial slot holds = 16 * MTMAX
@@ -92,62 +98,108 @@ struct FastArgs {
 #endif
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Accesses that go to the device's point of coherence (past the per-die L2), for the few KB that
+// workgroups hand to each other inside one launch.  64-bit relaxed device-scope atomics: the widest
+// form the compiler offers, and it can keep many of them in flight before it waits.
+__device__ __forceinline__ void coherent_store2(float* p, float x, float y) {
+    const unsigned long long bits = (unsigned long long)__builtin_bit_cast(uint32_t, x) | ((unsigned long long)__builtin_bit_cast(uint32_t, y) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_load2(const float* p, float& x, float& y) {
+    const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    x = __builtin_bit_cast(float, (uint32_t)bits);
+    y = __builtin_bit_cast(float, (uint32_t)(bits >> 32));
+}
+__device__ __forceinline__ void coherent_store4(float* p, f32x4 v) {
+    coherent_store2(p, v[0], v[1]);
+    coherent_store2(p + 2, v[2], v[3]);
+}
+__device__ __forceinline__ f32x4 coherent_load4(const float* p) {
+    float x, y, z, w;
+    coherent_load2(p, x, y);
+    coherent_load2(p + 2, z, w);
+    return f32x4{x, y, z, w};
+}
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
 // Swizzled byte offset of 16-byte chunk `ch` (0..15) of key row `key` in a [32][128] bf16 tile.
 __device__ __forceinline__ int vtile_off(int key, int ch) { return key * 256 + ((ch ^ ((key & 7) << 1)) << 4); }
 
 // ---------------------------------------------------------------------------------------
-// Schedule shared by the main and the fix-up kernel.
-// pref[i] = number of 32-key tiles of requests 0..i-1 (per KV head); item (i, g) owns the
-// flattened tiles [pref[i] * H_kv + g * nt_i, ... + nt_i).
+// Schedule.  Work is measured in cost units: a 32-key tile of request i costs cost[i] units,
+// more when more query-row tiles ride on it (1 + number of 16-row tiles), so that shares of
+// equal cost take about equal time whether a request has one suffix row or nine.
+// pref[i] = cost of the tiles of requests 0..i-1 for one KV head; item (i, g) with nt_i tiles
+// owns the flattened cost interval [pref[i] * H_kv + g * nt_i * cost[i], ... + nt_i * cost[i]).
 // ---------------------------------------------------------------------------------------
-__device__ void build_tile_prefix(const FastArgs& a, int* pref, int* scratch) {
+__device__ __forceinline__ int tile_cost(int rows_sharing_kv, int mt_max) {
+    const int mt = (rows_sharing_kv + 15) >> 4;
+    if (mt <= mt_max) return 1 + mt;
+    const int passes = (mt + mt_max - 1) / mt_max;  // such an item is done in passes by one workgroup
+    return min(passes * (1 + mt_max), 255);
+}
+
+// Returns the largest per-tile cost of any request.
+__device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, unsigned char* cost, long long* scratch) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int carry = 0;
+    long long carry = 0;
+    int cmax = 1;
     for (int base = 0; base < a.B; base += kThreads) {
         const int i = base + threadIdx.x;
-        int nt = 0;
+        long long units = 0;
         if (i < a.B) {
             const int ql = a.cu_q[i + 1] - a.cu_q[i];
+            int cst = 1;
             if (ql > 0) {
                 const int L = min(max(a.ctx[i], 0) + ql, a.max_pages * kP);
-                nt = (L + kTile - 1) / kTile;
+                cst = tile_cost(a.G * ql, mt_max);
+                units = (long long)((L + kTile - 1) / kTile) * cst;
             }
+            cost[i] = (unsigned char)cst;
+            cmax = max(cmax, cst);
         }
-        const int inc = wave_inclusive_scan(nt);
+        const long long inc = wave_inclusive_scan(units);
         if (lane == 63) scratch[w] = inc;
         __syncthreads();
-        int before = 0, total = 0;
+        long long before = 0, total = 0;
 #pragma unroll
         for (int k = 0; k < kWaves; ++k) {
             if (k < w) before += scratch[k];
             total += scratch[k];
         }
-        if (i < a.B) pref[i] = carry + before + inc - nt;
+        if (i < a.B) pref[i] = carry + before + inc - units;
         carry += total;
         __syncthreads();
     }
     if (threadIdx.x == 0) pref[a.B] = carry;
+    cmax = wave_max_i(cmax);
+    if (lane == 0) scratch[w] = cmax;
     __syncthreads();
+    cmax = (int)max(max(scratch[0], scratch[1]), max(scratch[2], scratch[3]));
+    __syncthreads();
+    return cmax;
 }
 
 struct Item {
-    int i, g, nt, tile;  // request, KV head, tiles of the item, tile inside the item
+    int i, g, nt, cost, tile;  // request, KV head, tiles of the item, cost of one tile, tile inside the item
+    long long base;            // flattened cost position of the item's first tile
 };
 
-__device__ __forceinline__ Item locate(const int* pref, int B, int H_kv, long long t) {
-    int lo = 0, hi = B;  // largest i with pref[i] * H_kv <= t
+__device__ __forceinline__ Item locate(const long long* pref, const unsigned char* cost, int B, int H_kv, long long x) {
+    int lo = 0, hi = B;  // largest i with pref[i] * H_kv <= x
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if ((long long)pref[mid] * H_kv <= t) lo = mid; else hi = mid;
+        if (pref[mid] * H_kv <= x) lo = mid; else hi = mid;
     }
     Item it;
     it.i = lo;
-    it.nt = pref[lo + 1] - pref[lo];
-    const int local = (int)(t - (long long)pref[lo] * H_kv);
-    it.g = local / it.nt;
-    it.tile = local - it.g * it.nt;
+    it.cost = cost[lo];
+    const long long item_units = pref[lo + 1] - pref[lo];
+    it.nt = (int)(item_units / it.cost);
+    const long long local = x - pref[lo] * H_kv;
+    it.g = (int)(local / item_units);
+    it.base = pref[lo] * H_kv + it.g * item_units;
+    it.tile = (int)((x - it.base) / it.cost);
     return it;
 }
 
@@ -156,41 +208,118 @@ struct KVTile {
     s16x8 v[8];
 };
 
-// One (request, KV head) item, tiles [tile_a, tile_e), query rows j0 .. j0 + rows_g - 1.
-// final_out: the tiles are the whole item -> normalise and write `out`; otherwise write a
-// partial into slot `slot`.
+// What a workgroup processes between two merges: tiles [tile_a, tile_e) of item (i, kvh) for the
+// query rows j0 .. j0 + rows_g - 1 of the request.  final_out: the tiles are the whole item, so
+// the result is normalised and written to `out`; otherwise it goes to partial slot `slot`.
+struct Segment {
+    int i, kvh, c, q0, q_len, j0, rows_g, tile_a, tile_e, slot;
+    bool final_out;
+};
+
+// One wave's view of a segment's K/V tiles: keys kb0 + t * (kWaves * kTile), t = 0 .. nw-1.
+struct KVStream {
+    const const_i32* bt;  // the request's block table, read through the constant address space so
+                          // that the (wave-uniform) page look-ups are scalar loads
+    const char* k_head;   // caches offset to the KV head
+    const char* v_head;
+    int kb0, nw, kv_total, kend;
+};
+
+constexpr int kStep = kWaves * kTile;
+
+// Values that are the same in every lane, moved to scalar registers: addresses built from them
+// are scalar, and loads through them (the page look-ups) are scalar loads that never wait on the
+// vector-memory queue.
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ __forceinline__ T* uniform(T* p) {
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return reinterpret_cast<T*>(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ const const_i32* uniform(const const_i32* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const const_i32*)(((unsigned long long)hi << 32) | lo);
+}
+
+__device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment& sg) {
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    KVStream st;
+    st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
+    const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
+    st.k_head = reinterpret_cast<const char*>(a.k) + (size_t)kvh * kP * kD * 2;
+    st.v_head = reinterpret_cast<const char*>(a.v) + (size_t)kvh * kP * kD * 2;
+    const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
+    st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
+    const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
+    // keys any row of this pass may see
+    st.kend = min(min(__builtin_amdgcn_readfirstlane(sg.tile_e) * kTile,
+                      c + __builtin_amdgcn_readfirstlane(sg.j0) + __builtin_amdgcn_readfirstlane(sg.rows_g)), st.kv_total);
+    st.kb0 = kbeg + w * kTile;
+    st.nw = st.kb0 < st.kend ? (st.kend - st.kb0 + kStep - 1) / kStep : 0;
+    return st;
+}
+
+// Issue the global loads of the wave's tile ti (no waiting).  Tiles past the wave's last one are
+// "issued" too, so that the number of loads in flight is the same on every path and the compiler's
+// wait counts stay exact: all their lanes read the first bytes of the last tile (16 cache lines,
+// already resident) and nothing consumes them.  Needs st.nw > 0.
+__device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, KVTile& t, int ti) {
+    const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
+    KVStream st;
+    st.bt = uniform(sv.bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
+    st.kb0 = uniform(sv.kb0); st.nw = uniform(sv.nw); st.kv_total = uniform(sv.kv_total);
+    ti = uniform(ti);
+    const bool real = ti < st.nw;
+    const int kb = st.kb0 + min(ti, st.nw - 1) * kStep;
+    // per-lane byte offsets inside a 4 KB (page, head) block: every load is then
+    // "uniform base + this offset + immediate", with no per-load address arithmetic
+    const int kl = real ? li * 256 + lg * 16 : 0;  // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
+    const int vl = real ? lg * 256 + li * 16 : 0;  // V: key lg (+ 4 r), 16-byte chunk li
+    const size_t page_bytes = (size_t)a.H_kv * kP * kD * 2;
+    // the second page exists only if the request has tokens there
+    int pg0 = st.bt[kb >> 4];
+    int pg1 = (kb + kP < st.kv_total) ? st.bt[(kb >> 4) + 1] : pg0;
+    pg0 = min(max(pg0, 0), a.n_pages - 1);
+    pg1 = min(max(pg1, 0), a.n_pages - 1);
+    const char* kp0 = st.k_head + (size_t)pg0 * page_bytes;
+    const char* kp1 = st.k_head + (size_t)pg1 * page_bytes;
+    const char* vp0 = st.v_head + (size_t)pg0 * page_bytes;
+    const char* vp1 = st.v_head + (size_t)pg1 * page_bytes;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        t.k[0][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp0 + kl + 64 * kk));
+        t.k[1][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp1 + kl + 64 * kk));
+    }
+    // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        t.v[r] = *reinterpret_cast<const s16x8*>(vp0 + vl + 1024 * r);
+        t.v[4 + r] = *reinterpret_cast<const s16x8*>(vp1 + vl + 1024 * r);
+    }
+}
+
+// Process one segment: stream the wave's tiles, merge the 4 waves, write the result or the partial.
 template <int MT>
-__device__ void attend_segment(const FastArgs& a, int i, int kvh, int c, int q0, int q_len, int j0, int rows_g,
-                               int tile_a, int tile_e, bool final_out, int slot, char* smem, int seg_no = 0) {
+__device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem, int seg_no) {
     FSR_STAMP(seg_no * 5 + 2);
-    // everything that is the same for the whole wave goes to scalar registers, so that the key
-    // loop's page look-ups are scalar loads and never wait on the vector-memory queue
-    i = __builtin_amdgcn_readfirstlane(i);
-    kvh = __builtin_amdgcn_readfirstlane(kvh);
-    c = __builtin_amdgcn_readfirstlane(c);
-    q0 = __builtin_amdgcn_readfirstlane(q0);
-    q_len = __builtin_amdgcn_readfirstlane(q_len);
-    j0 = __builtin_amdgcn_readfirstlane(j0);
-    rows_g = __builtin_amdgcn_readfirstlane(rows_g);
-    tile_a = __builtin_amdgcn_readfirstlane(tile_a);
-    tile_e = __builtin_amdgcn_readfirstlane(tile_e);
+    // everything that is the same for the whole wave goes to scalar registers
+    const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
+    const int c = __builtin_amdgcn_readfirstlane(sg.c);
+    const int q0 = __builtin_amdgcn_readfirstlane(sg.q0);
+    const int j0 = __builtin_amdgcn_readfirstlane(sg.j0);
+    const int rows_g = __builtin_amdgcn_readfirstlane(sg.rows_g);
+    const bool final_out = sg.final_out;
+    const int slot = sg.slot;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lg = lane >> 4, li = lane & 15;
     const int G = a.G;
     const int M_g = G * rows_g;
-    const int kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
-    const int kbeg = tile_a * kTile;
-    const int kend = min(min(tile_e * kTile, c + j0 + rows_g), kv_total);  // keys any row of this pass may see
+    const int kv_total = uniform(st.kv_total), kb0 = uniform(st.kb0), nw = uniform(st.nw);
     char* vbuf = smem + w * kVTileBytes;
 
-    // the block table is read-only input: reading it through the constant address space lets the
-    // compiler use scalar loads for the (wave-uniform) page look-ups
-    const const_i32* bt = (const const_i32*)(a.bt + (size_t)i * a.max_pages);
-    // per-lane byte offsets inside a 4 KB (page, head) block: every load below is then
-    // "uniform base + this offset + immediate", with no per-load address arithmetic
-    const int k_lane = li * 256 + lg * 16;          // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
-    const int v_lane = lg * 256 + li * 16;          // V: key lg (+ 4 r), 16-byte chunk li
     const int vw_even = vtile_off(lg, li), vw_odd = vtile_off(4 + lg, li) - 4 * 256;  // LDS store offsets (+ 1024 r)
     // LDS transposed-read offsets: lane (lg, li) reads 8 bytes of key row 16 h + 4 lg + li/4 at
     // d = 16 db + 4 (li%4); after the transpose it holds keys 16 h + 4 lg + 0..3 at d = 16 db + li
@@ -200,45 +329,7 @@ __device__ void attend_segment(const FastArgs& a, int i, int kvh, int c, int q0,
 #pragma unroll
         for (int db = 0; db < 8; ++db) vr_off[db] = vtile_off(r0, 2 * db + ((li & 3) >> 1)) + (li & 1) * 8;
     }
-    const size_t page_bytes = (size_t)a.H_kv * kP * kD * 2;
-    const char* k_head = reinterpret_cast<const char*>(a.k) + (size_t)kvh * kP * kD * 2;
-    const char* v_head = reinterpret_cast<const char*>(a.v) + (size_t)kvh * kP * kD * 2;
-
-    // this wave's tiles: keys kb0 + t * kStep, t = 0 .. nw-1
-    constexpr int kStep = kWaves * kTile;
-    const int kb0 = kbeg + w * kTile;
-    const int nw = kb0 < kend ? (kend - kb0 + kStep - 1) / kStep : 0;
-
-    // ---- issue the global loads of this wave's tile t (no waiting).  Tiles past the wave's last
-    // one are "issued" too, so that the number of loads in flight is the same on every path and
-    // the compiler's wait counts stay exact: all their lanes read the first bytes of the last tile
-    // (16 cache lines, already resident) and nothing consumes them.
-    auto issue = [&](KVTile& t, int ti) {
-        const bool real = ti < nw;
-        const int kb = kb0 + min(ti, nw - 1) * kStep;
-        const int kl = real ? k_lane : 0, vl = real ? v_lane : 0;
-        // the second page exists only if the request has tokens there
-        int pg0 = bt[kb >> 4];
-        int pg1 = (kb + kP < kv_total) ? bt[(kb >> 4) + 1] : pg0;
-        pg0 = min(max(pg0, 0), a.n_pages - 1);
-        pg1 = min(max(pg1, 0), a.n_pages - 1);
-        const char* kp0 = k_head + (size_t)pg0 * page_bytes;
-        const char* kp1 = k_head + (size_t)pg1 * page_bytes;
-        const char* vp0 = v_head + (size_t)pg0 * page_bytes;
-        const char* vp1 = v_head + (size_t)pg1 * page_bytes;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            t.k[0][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp0 + kl + 64 * kk));
-            t.k[1][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp1 + kl + 64 * kk));
-        }
-        // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            t.v[r] = *reinterpret_cast<const s16x8*>(vp0 + vl + 1024 * r);
-            t.v[4 + r] = *reinterpret_cast<const s16x8*>(vp1 + vl + 1024 * r);
-        }
-    };
-
+    auto issue = [&](KVTile& t, int ti) { issue_tile(a, st, t, ti); };
     // The K/V stream does not depend on Q: start it before anything else of the segment.
     KVTile ta, tb;
     if (nw > 0) {
@@ -578,13 +669,14 @@ __device__ void attend_segment(const FastArgs& a, int i, int kvh, int c, int q0,
                     }
                     if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (ms + __log2f(ls)) * kLn2;
                 } else {
+                    // pieces are read by another workgroup of this launch, possibly on another die:
+                    // device-coherent stores (and loads on the other side) instead of cache flushes
                     float* dst = a.part_o + ((size_t)slot * a.m_cap + m) * kD + d0;
-                    *reinterpret_cast<f32x4*>(dst) = s0;
-                    *reinterpret_cast<f32x4*>(dst + 4) = s1;
+                    coherent_store4(dst, s0);
+                    coherent_store4(dst + 4, s1);
                     if (d0 == 0) {
                         float* ml = a.part_ml + ((size_t)slot * a.m_cap + m) * 2;
-                        ml[0] = ms;
-                        ml[1] = ls;
+                        coherent_store2(ml, ms, ls);
                     }
                 }
             }
@@ -594,10 +686,10 @@ __device__ void attend_segment(const FastArgs& a, int i, int kvh, int c, int q0,
 }
 
 template <int MTMAX>
-__device__ __forceinline__ void attend_dispatch(const FastArgs& a, int mt, int i, int kvh, int c, int q0, int q_len,
-                                                int j0, int rows_g, int tile_a, int tile_e, bool final_out, int slot,
-                                                char* smem, int seg_no = 0) {
-#define FSR_SEG(MT) attend_segment<MT>(a, i, kvh, c, q0, q_len, j0, rows_g, tile_a, tile_e, final_out, slot, smem, seg_no)
+__device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem,
+                                                int seg_no) {
+    const int mt = (a.G * sg.rows_g + 15) >> 4;
+#define FSR_SEG(MT) attend_segment<MT>(a, sg, st, smem, seg_no)
     if constexpr (MTMAX == 1) {
         FSR_SEG(1);
     } else if constexpr (MTMAX == 2) {
@@ -612,94 +704,42 @@ __device__ __forceinline__ void attend_dispatch(const FastArgs& a, int mt, int i
 #undef FSR_SEG
 }
 
-// Persistent grid: nb workgroups of 256 threads; workgroup b takes flattened tiles
-// [b T / nb', (b+1) T / nb') with nb' = min(nb, T).
-template <int MTMAX>
-__global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* pref = reinterpret_cast<int*>(smem + kPrefOff);
-    FSR_STAMP(0);
-#ifdef FSR_TIMING
-    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 126 * 4] = clock64();
-#endif
-    build_tile_prefix(a, pref, reinterpret_cast<int*>(smem + kScanOff));
-    FSR_STAMP(1);
-    const long long T = (long long)pref[a.B] * a.H_kv;
-    const int nb = (int)min((long long)a.nb, T);
-    const int b = blockIdx.x;
-    if (b >= nb) return;
-    long long t = (long long)b * T / nb;
-    const long long t1 = (long long)(b + 1) * T / nb;
-    int seg_no = 0;
-    while (t < t1) {
-        const Item it = locate(pref, a.B, a.H_kv, t);
-        const int tile_e = (int)min((long long)it.nt, it.tile + (t1 - t));
-        const int q0 = a.cu_q[it.i], q_len = a.cu_q[it.i + 1] - q0;
-        const int c = max(a.ctx[it.i], 0);
-        const int rows = a.G * q_len;
-        if (rows <= 16 * MTMAX) {
-            const bool whole = it.tile == 0 && tile_e == it.nt;
-            const int slot = b * 2 + (it.tile > 0 ? 0 : 1);
-            attend_dispatch<MTMAX>(a, (rows + 15) >> 4, it.i, it.g, c, q0, q_len, 0, q_len, it.tile, tile_e, whole, slot, smem, min(seg_no, 2));
-            ++seg_no;
-        } else if (it.tile == 0) {
-            // more rows than a partial slot holds: the workgroup owning the item's first tile does
-            // the whole item, in passes over groups of rows; the other workgroups skip it
-            const int rows_per_pass = (16 * MTMAX) / a.G;
-            for (int j0 = 0; j0 < q_len; j0 += rows_per_pass) {
-                const int rows_g = min(rows_per_pass, q_len - j0);
-                attend_dispatch<MTMAX>(a, (a.G * rows_g + 15) >> 4, it.i, it.g, c, q0, q_len, j0, rows_g, 0, it.nt, true, 0, smem);
-            }
-        }
-        t += tile_e - it.tile;
-    }
-    FSR_STAMP(15);
-#ifdef FSR_TIMING
-    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 127 * 4] = clock64();
-#endif
-}
-
-// Combine the partials of items cut by share boundaries.  grid = nb.  Workgroup b is
-// responsible for the item that contains its first tile if that item starts inside the
-// previous workgroup's share; the pieces are then slot 1 of b-1 and slot 0 of b, b+1, ...
-// while their shares start inside the item.
-__global__ __launch_bounds__(kThreads) void attn_fixup_kernel(FastArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    int* pref = reinterpret_cast<int*>(smem + kPrefOff);
-    build_tile_prefix(a, pref, reinterpret_cast<int*>(smem + kScanOff));
-    const long long T = (long long)pref[a.B] * a.H_kv;
-    const int nb = (int)min((long long)a.nb, T);
-    const int b = blockIdx.x;
-    if (b == 0 || b >= nb) return;
-    const long long t0 = (long long)b * T / nb;
-    const Item it = locate(pref, a.B, a.H_kv, t0);
-    if (it.tile == 0) return;                       // the boundary falls between two items
-    const long long item_start = t0 - it.tile, item_end = item_start + it.nt;
-    if (item_start < (long long)(b - 1) * T / nb) return;  // an earlier workgroup is responsible
-    const int q0 = a.cu_q[it.i], q_len = a.cu_q[it.i + 1] - q0;
-    const int M = a.G * q_len;
-    if (M > a.m_cap) return;                        // such items are never cut
-    int b_last = b;
-    while (b_last + 1 < nb && (long long)(b_last + 1) * T / nb < item_end) ++b_last;
+// Combine the pieces of an item that share boundaries cut: slot 1 of workgroup b_first (which holds
+// the item's first tile) and slot 0 of b_first+1 .. b_last.  Called by one whole workgroup.
+__device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int g, int q0, int M) {
+    constexpr int kBatch = 4;  // pieces whose loads are in flight together
     for (int e = threadIdx.x; e < M * (kD / 4); e += kThreads) {
         const int m = e / (kD / 4), d0 = (e % (kD / 4)) * 4;
-        float m_star = -INFINITY;
-        for (int bb = b - 1; bb <= b_last; ++bb) {
-            const int slot = bb * 2 + (bb == b - 1 ? 1 : 0);
-            m_star = fmaxf(m_star, a.part_ml[((size_t)slot * a.m_cap + m) * 2]);
-        }
-        const float mu = m_star == -INFINITY ? 0.0f : m_star;
+        float m_star = -INFINITY, l = 0.0f;
         f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-        float l = 0.0f;
-        for (int bb = b - 1; bb <= b_last; ++bb) {
-            const int slot = bb * 2 + (bb == b - 1 ? 1 : 0);
-            const float* ml = a.part_ml + ((size_t)slot * a.m_cap + m) * 2;
-            const float wgt = fast_exp2(ml[0] - mu);
-            l += ml[1] * wgt;
-            o += *reinterpret_cast<const f32x4*>(a.part_o + ((size_t)slot * a.m_cap + m) * kD + d0) * wgt;
+        for (int bb0 = b_first; bb0 <= b_last; bb0 += kBatch) {
+            float pm[kBatch], pl[kBatch];
+            f32x4 po[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int bb = min(bb0 + k, b_last);  // past the end: the last piece again, weighted 0 below
+                const size_t row = (size_t)(bb * 2 + (bb == b_first ? 1 : 0)) * a.m_cap + m;
+                coherent_load2(a.part_ml + row * 2, pm[k], pl[k]);
+                po[k] = coherent_load4(a.part_o + row * kD + d0);
+            }
+            float m_new = m_star;
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                if (bb0 + k <= b_last) m_new = fmaxf(m_new, pm[k]);
+            const float mu = m_new == -INFINITY ? 0.0f : m_new;
+            const float keep = fast_exp2(m_star - mu);  // 0 while nothing has been accumulated
+            l *= keep;
+            o *= keep;
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const float wgt = bb0 + k <= b_last ? fast_exp2(pm[k] - mu) : 0.0f;
+                l += pl[k] * wgt;
+                o += po[k] * wgt;
+            }
+            m_star = m_new;
         }
         o *= 1.0f / l;
-        const int j = m / a.G, h = it.g * a.G + m % a.G;
+        const int j = m / a.G, h = g * a.G + m % a.G;
         const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
         if (a.out_bf16) {
             ushort4 pk;
@@ -713,6 +753,142 @@ __global__ __launch_bounds__(kThreads) void attn_fixup_kernel(FastArgs a) {
         }
         if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (m_star + __log2f(l)) * kLn2;
     }
+}
+
+// One more piece of a cut item is in memory: count it.  The word holds (call id << 16 | count); a
+// word left by another call (or never written) counts as zero, so the workspace needs no clearing.
+__device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned long long call_id) {
+    unsigned long long seen = __atomic_load_n(word, __ATOMIC_RELAXED);
+    for (;;) {
+        const unsigned long long have = (seen >> 16) == call_id ? (seen & 0xffffu) : 0u;
+        const unsigned long long want = (call_id << 16) | (have + 1);
+        const unsigned long long prev = atomicCAS(word, seen, want);
+        if (prev == seen) return (int)(have + 1);
+        seen = prev;
+    }
+}
+
+// Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
+struct ShareWalker {
+    const long long* pref;
+    const unsigned char* cost;
+    long long x, x1, T;
+    int nb, b, mt_max, pass_j0;
+    // what the segment just handed out is part of (for counting the pieces of a cut item)
+    long long item_base, item_end;
+    int item_cost, item_rows;
+    bool cut;
+
+    __device__ long long share_start(int bb) const { return (long long)bb * T / nb; }
+    __device__ int owner_of(long long upto) const {  // largest bb with share_start(bb) < upto
+        int bb = (int)((upto - 1) * nb / T);
+        while (bb + 1 < nb && share_start(bb + 1) < upto) ++bb;
+        while (bb > 0 && share_start(bb) >= upto) --bb;
+        return bb;
+    }
+    // Next segment of the share; false when the share is exhausted.
+    __device__ bool next(const FastArgs& a, Segment& sg) {
+        while (x < x1) {
+            const Item it = locate(pref, cost, a.B, a.H_kv, x);
+            const long long iend = it.base + (long long)it.nt * it.cost;
+            const int tile_e = x1 >= iend ? it.nt : (int)((x1 - it.base) / it.cost);
+            // scalar loads (constant address space, uniform index): they must not queue behind the K/V
+            // tile loads that are in flight while the next segment is being looked up
+            const int ri = uniform(it.i);
+            const const_i32* cu = (const const_i32*)a.cu_q;
+            const const_i32* cx = (const const_i32*)a.ctx;
+            const int q0 = cu[ri], q_len = cu[ri + 1] - q0;
+            const int rows = a.G * q_len;
+            sg.i = ri; sg.kvh = uniform(it.g); sg.c = max((int)cx[ri], 0); sg.q0 = q0; sg.q_len = q_len;
+            item_base = it.base; item_end = iend; item_cost = it.cost; item_rows = rows;
+            if (tile_e > it.tile) {
+                if (rows <= 16 * mt_max) {
+                    sg.j0 = 0; sg.rows_g = q_len; sg.tile_a = it.tile; sg.tile_e = tile_e;
+                    sg.final_out = it.tile == 0 && tile_e == it.nt;
+                    sg.slot = b * 2 + (it.tile > 0 ? 0 : 1);
+                    cut = !sg.final_out;
+                    x = x1 >= iend ? iend : x1;
+                    return true;
+                }
+                if (it.tile == 0) {
+                    // more rows than a partial slot holds: the workgroup owning the item's first tile
+                    // does the whole item, in passes over groups of rows; the other workgroups skip it
+                    const int rows_per_pass = (16 * mt_max) / a.G;
+                    if (pass_j0 < q_len) {
+                        sg.j0 = pass_j0; sg.rows_g = min(rows_per_pass, q_len - pass_j0); sg.tile_a = 0; sg.tile_e = it.nt;
+                        sg.final_out = true; sg.slot = 0;
+                        cut = false;
+                        pass_j0 += rows_per_pass;
+                        if (pass_j0 >= q_len) {
+                            pass_j0 = 0;
+                            x = x1 >= iend ? iend : x1;
+                        }
+                        return true;
+                    }
+                }
+            }
+            x = x1 >= iend ? iend : x1;
+        }
+        return false;
+    }
+};
+
+// Persistent grid: nb workgroups of 256 threads; workgroup b takes the share
+// [b T / nb', (b+1) T / nb') of the cost line, nb' = min(nb, T / dearest tile).  An item that lies
+// inside one share is finished by that workgroup; an item cut by share boundaries leaves one
+// partial per piece, and the workgroup whose piece arrives last combines them (no workgroup ever
+// waits for another).
+template <int MTMAX>
+__global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_last;
+    long long* pref = reinterpret_cast<long long*>(smem + kPrefOff);
+    unsigned char* cost = reinterpret_cast<unsigned char*>(smem + kCostOff);
+    FSR_STAMP(0);
+#ifdef FSR_TIMING
+    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 126 * 4] = clock64();
+#endif
+    const int cmax = build_cost_prefix(a, MTMAX, pref, cost, reinterpret_cast<long long*>(smem + kScanOff));
+    FSR_STAMP(1);
+    ShareWalker wk;
+    wk.pref = pref; wk.cost = cost;
+    wk.T = pref[a.B] * a.H_kv;
+    // every share is at least as wide as the dearest tile, so every workgroup owns at least one tile
+    wk.nb = (int)min((long long)a.nb, wk.T / cmax);
+    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.pass_j0 = 0; wk.cut = false;
+    if (wk.b >= wk.nb) return;
+    wk.x = wk.share_start(wk.b);
+    wk.x1 = wk.share_start(wk.b + 1);
+
+    Segment cur;
+    int seg_no = 0;
+    while (wk.next(a, cur)) {
+        const KVStream st = make_stream(a, cur);
+        attend_dispatch<MTMAX>(a, cur, st, smem, min(seg_no, 2));
+        ++seg_no;
+        if (wk.cut) {
+            // pieces of this item: the workgroups that own its first .. last tile; workgroup bb owns
+            // tile k iff share_start(bb) < base + (k + 1) * cost <= share_start(bb + 1)
+            const int b_first = wk.owner_of(wk.item_base + wk.item_cost), b_last = wk.owner_of(wk.item_end);
+            // the piece's stores are device-coherent; once every wave has seen them acknowledged the
+            // piece may be counted
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (threadIdx.x == 0) s_last = count_arrival(a.arrivals + b_first + 1, a.call_id) == b_last - b_first + 1;
+            __syncthreads();
+            FSR_STAMP(100 + min(seg_no - 1, 1) * 2);
+            if (s_last) {
+                combine_cut_item(a, b_first, b_last, cur.kvh, cur.q0, wk.item_rows);
+                if (threadIdx.x == 0) __atomic_store_n(a.arrivals + b_first + 1, a.call_id << 16, __ATOMIC_RELAXED);
+            }
+            __syncthreads();
+            FSR_STAMP(101 + min(seg_no - 1, 1) * 2);
+        }
+    }
+    FSR_STAMP(15);
+#ifdef FSR_TIMING
+    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 127 * 4] = clock64();
+#endif
 }
 
 __device__ __forceinline__ int find_request(const int32_t* __restrict__ cu_q, int B, int row) {
@@ -806,7 +982,7 @@ struct Plan {
     bool fast;
     int mt_max;  // 16-row query tiles per pass of the fast kernel
     int nb;      // workgroups of the persistent grid
-    size_t bytes_o, bytes_ml;
+    size_t bytes_o, bytes_ml, bytes_cnt;
 };
 
 int validate(const fsr_attn_params* p, const char* who) {
@@ -824,6 +1000,12 @@ int validate(const fsr_attn_params* p, const char* who) {
     if (p->B > 65535 || p->H_kv > 65535) return fail(FSR_EUNSUP, "%s: B and H_kv are limited to 65535", who);
     if ((long long)p->max_pages * p->P > (1LL << 30)) return fail(FSR_EUNSUP, "%s: max_pages * P exceeds 2^30 tokens", who);
     return FSR_OK;
+}
+
+// A number no earlier call of this process has used (48 bits, never 0).
+unsigned long long next_call_id() {
+    static std::atomic<unsigned long long> counter{0};
+    return (counter.fetch_add(1, std::memory_order_relaxed) + 1) & 0xffffffffffffull;
 }
 
 // Workgroups of the persistent grid: one per compute unit of the current device.
@@ -859,6 +1041,7 @@ Plan make_plan(const fsr_attn_params& p) {
     pl.nb = std::min(persistent_blocks(), 1024);
     pl.bytes_o = align_up((size_t)1024 * 2 * 16 * pl.mt_max * kD * sizeof(float), 256);
     pl.bytes_ml = align_up((size_t)1024 * 2 * 16 * pl.mt_max * 2 * sizeof(float), 256);
+    pl.bytes_cnt = align_up((size_t)(1024 + 1) * sizeof(unsigned long long), 256);
     return pl;
 }
 
@@ -872,7 +1055,7 @@ extern "C" int fsr_attn_workspace_bytes(const fsr_attn_params* p, size_t* out_by
     if (rc != FSR_OK) return rc;
     if (!out_bytes) return fail(FSR_EINVAL, "fsr_attn_workspace_bytes: out_bytes is null");
     const Plan pl = make_plan(*p);
-    *out_bytes = pl.fast ? pl.bytes_o + pl.bytes_ml : 0;
+    *out_bytes = pl.fast ? pl.bytes_o + pl.bytes_ml + pl.bytes_cnt : 0;
     return FSR_OK;
 }
 
@@ -889,7 +1072,7 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
     hipStream_t s = (hipStream_t)stream;
     const Plan pl = make_plan(*p);
     if (pl.fast) {
-        const size_t need = pl.bytes_o + pl.bytes_ml;
+        const size_t need = pl.bytes_o + pl.bytes_ml + pl.bytes_cnt;
         if (!workspace || ws_bytes < need) return fail(FSR_EWS, "fsr_verify_attention: workspace %zu bytes, need %zu", ws_bytes, need);
         if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "fsr_verify_attention: workspace must be 256-byte aligned");
         if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15)
@@ -900,6 +1083,8 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
         a.out = out; a.lse = lse;
         a.part_o = (float*)workspace;
         a.part_ml = (float*)((char*)workspace + pl.bytes_o);
+        a.arrivals = (unsigned long long*)((char*)workspace + pl.bytes_o + pl.bytes_ml);
+        a.call_id = next_call_id();
         a.B = p->B; a.H_q = p->H_q; a.H_kv = p->H_kv; a.G = p->H_q / p->H_kv;
         a.max_pages = p->max_pages; a.n_pages = p->n_pages;
         a.nb = pl.nb; a.m_cap = 16 * pl.mt_max; a.out_bf16 = p->out_dtype == FSR_BF16;
@@ -915,9 +1100,7 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
             case 4: hipLaunchKernelGGL(attn_stream_kernel<4>, grid, block, kFastSmem, s, a); break;
             default: hipLaunchKernelGGL(attn_stream_kernel<6>, grid, block, kFastSmem, s, a); break;
         }
-        if ((rc = check_launch("attn_stream_kernel")) != FSR_OK) return rc;
-        hipLaunchKernelGGL(attn_fixup_kernel, grid, block, kFastSmem, s, a);
-        return check_launch("attn_fixup_kernel");
+        return check_launch("attn_stream_kernel");
     }
     GenericArgs g;
     g.q = q; g.k = k_cache; g.v = v_cache; g.bt = block_tables; g.ctx = ctx_lens; g.cu_q = cu_q; g.out = out; g.lse = lse;
