@@ -109,6 +109,19 @@ def cpu_baseline(b, n_layers):
                        f"compaction ({t_pr * 1e3:.2f} ms) at full size"), r
 
 
+def measured_traffic():
+    """HBM bytes per attention launch from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, scaled by a plain copy of known size), or None if there is no summary."""
+    path = os.path.join(ROOT, "profiles", "attn_stream_kernel_cfg2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +130,9 @@ def main():
     ap.add_argument("--layers", type=int, default=N_LAYERS)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that hardware byte counters of a "
+                         "profiled run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -130,6 +146,14 @@ def main():
     torch.cuda.set_device(0)
     b = workloads.make_batch(2)
     step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002)
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     stream = torch.cuda.Stream()
     graph = None
@@ -189,9 +213,9 @@ def main():
                    "layers_per_step": args.layers, "rows": b.N, "drafts_per_step": drafts,
                    "kv_tokens": b.kv_tokens(), "launch": "hip_graph" if graph is not None else "eager",
                    "attention_ms_per_layer": attn_ms, "accept_prune_ms": tail_ms, "seed": b.seed},
-        "roofline": {"bound": "hbm", "kernel": "verify_attention (attn_fast_kernel + split merge)",
+        "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel (verify_attention, one launch per layer call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": attn_bytes,
+                     "traffic": measured_traffic(), "algorithmic_bytes_per_launch": attn_bytes,
                      "launch_us": attn_ms * 1e3},
     }
     if not args.no_cpu_baseline:

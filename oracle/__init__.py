@@ -125,7 +125,7 @@ def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None):
         pay = np.ascontiguousarray(payload)
         assert pay.shape[0] == N
         row_bytes = pay.nbytes // max(N, 1) if N else 0
-        pin = pay.view(np.uint8).reshape(N, -1) if N else np.zeros((0, 0), np.uint8)
+        pin = pay.view(np.uint8).reshape(N, row_bytes) if N else np.zeros((0, 0), np.uint8)
         pout = np.zeros_like(pin)
     lib.fo_prune_compact(_p(keep), _p(cu), _p(new_cu), _p(new_len), _p(src), _p(dst), _p(n_act), _p(act),
                          _p(pin), _p(pout), ctypes.c_int64(row_bytes), ctypes.c_int(B),
@@ -146,7 +146,7 @@ def prune_restore(compact, dst_row, *, pad_byte=0):
     comp = np.ascontiguousarray(compact)
     row_shape = comp.shape[1:]
     row_bytes = int(np.prod(row_shape)) * comp.dtype.itemsize
-    cin = comp.view(np.uint8).reshape(comp.shape[0], -1)
+    cin = comp.view(np.uint8).reshape(comp.shape[0], row_bytes)
     out = np.zeros((N, row_bytes), np.uint8)
     has = np.zeros(N, np.uint8)
     lib.fo_prune_restore(_p(cin), _p(dst), _p(out), _p(has), ctypes.c_int64(row_bytes), ctypes.c_int(N),
