@@ -65,6 +65,8 @@ constexpr int kCostOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
 constexpr int kCostBytes = ((kMaxB + 15) / 16) * 16;  // per-request cost of one tile (bytes)
 constexpr int kScanOff = kCostOff + kCostBytes;
 constexpr int kFastSmem = kScanOff + 64;
+constexpr int kCostBase = 1;  // a tile costs kCostBase + (16-row query tiles riding on it)
+constexpr int kSegTiles = 8;  // what starting an item costs a workgroup (merge, refill), in tiles of that item
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -86,6 +88,8 @@ struct FastArgs {
     int m_cap;       // rows (G * q_len) a partial slot holds = 16 * MTMAX
     int out_bf16;
     float scale_log2;
+    int cost_base;   // fixed part of a tile's cost (see tile_cost)
+    int seg_tiles;   // phantom tiles in front of every item on the cost line (see the schedule)
 #ifdef FSR_TIMING
     long long* dbg;  // [nb][128 slots][4 waves] timestamps (100 MHz)
 #endif
@@ -129,14 +133,19 @@ __device__ __forceinline__ int vtile_off(int key, int ch) { return key * 256 + (
 // Schedule.  Work is measured in cost units: a 32-key tile of request i costs cost[i] units,
 // more when more query-row tiles ride on it (1 + number of 16-row tiles), so that shares of
 // equal cost take about equal time whether a request has one suffix row or nine.
+// In front of its real tiles every item carries seg_tiles phantom tiles: they stand for what it
+// costs a workgroup to take up an item at all (merging its waves, refilling the load pipeline),
+// so a workgroup whose share spans an item boundary is handed fewer real tiles than one that
+// streams a single item throughout.
 // pref[i] = cost of the tiles of requests 0..i-1 for one KV head; item (i, g) with nt_i tiles
-// owns the flattened cost interval [pref[i] * H_kv + g * nt_i * cost[i], ... + nt_i * cost[i]).
+// (phantom ones included) owns the flattened cost interval
+// [pref[i] * H_kv + g * nt_i * cost[i], ... + nt_i * cost[i]).
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int tile_cost(int rows_sharing_kv, int mt_max) {
+__device__ __forceinline__ int tile_cost(int rows_sharing_kv, int mt_max, int base) {
     const int mt = (rows_sharing_kv + 15) >> 4;
-    if (mt <= mt_max) return 1 + mt;
+    if (mt <= mt_max) return base + mt;
     const int passes = (mt + mt_max - 1) / mt_max;  // such an item is done in passes by one workgroup
-    return min(passes * (1 + mt_max), 255);
+    return min(passes * (base + mt_max), 255);
 }
 
 // Returns the largest per-tile cost of any request.
@@ -152,8 +161,8 @@ __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref,
             int cst = 1;
             if (ql > 0) {
                 const int L = min(max(a.ctx[i], 0) + ql, a.max_pages * kP);
-                cst = tile_cost(a.G * ql, mt_max);
-                units = (long long)((L + kTile - 1) / kTile) * cst;
+                cst = tile_cost(a.G * ql, mt_max, a.cost_base);
+                units = (long long)((L + kTile - 1) / kTile + a.seg_tiles) * cst;
             }
             cost[i] = (unsigned char)cst;
             cmax = max(cmax, cst);
@@ -181,9 +190,17 @@ __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref,
 }
 
 struct Item {
-    int i, g, nt, cost, tile;  // request, KV head, tiles of the item, cost of one tile, tile inside the item
-    long long base;            // flattened cost position of the item's first tile
+    int i, g, nt, cost, tile;  // request, KV head, tiles of the item and the position's tile (both counting the
+                               // phantom tiles in front), cost of one tile
+    long long base;            // flattened cost position of the item's first (phantom) tile
 };
+
+// Quotient of two non-negative numbers; nearly always both fit 32 bits, where the division is an
+// order of magnitude cheaper than the 64-bit one.
+__device__ __forceinline__ long long div_u(long long n, long long d) {
+    if ((((unsigned long long)n | (unsigned long long)d) >> 32) == 0) return (long long)((unsigned)n / (unsigned)d);
+    return n / d;
+}
 
 __device__ __forceinline__ Item locate(const long long* pref, const unsigned char* cost, int B, int H_kv, long long x) {
     int lo = 0, hi = B;  // largest i with pref[i] * H_kv <= x
@@ -195,11 +212,11 @@ __device__ __forceinline__ Item locate(const long long* pref, const unsigned cha
     it.i = lo;
     it.cost = cost[lo];
     const long long item_units = pref[lo + 1] - pref[lo];
-    it.nt = (int)(item_units / it.cost);
+    it.nt = (int)div_u(item_units, it.cost);
     const long long local = x - pref[lo] * H_kv;
-    it.g = (int)(local / item_units);
+    it.g = (int)div_u(local, item_units);
     it.base = pref[lo] * H_kv + it.g * item_units;
-    it.tile = (int)((x - it.base) / it.cost);
+    it.tile = (int)div_u(x - it.base, it.cost);
     return it;
 }
 
@@ -237,6 +254,10 @@ __device__ __forceinline__ T* uniform(T* p) {
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
     return reinterpret_cast<T*>(((unsigned long long)hi << 32) | lo);
 }
+__device__ __forceinline__ long long uniform(long long x) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)x), hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)x >> 32));
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
 __device__ __forceinline__ const const_i32* uniform(const const_i32* p) {
     const unsigned long long v = (unsigned long long)p;
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
@@ -265,6 +286,78 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
 // "issued" too, so that the number of loads in flight is the same on every path and the compiler's
 // wait counts stay exact: all their lanes read the first bytes of the last tile (16 cache lines,
 // already resident) and nothing consumes them.  Needs st.nw > 0.
+// Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
+struct ShareWalker {
+    const long long* pref;
+    const unsigned char* cost;
+    long long x, x1, T, q;
+    int nb, r, b, mt_max, pass_j0, seg_tiles;
+    // what the segment just handed out is part of (for counting the pieces of a cut item)
+    long long first_end, item_end;  // cost position where the item's first real tile ends / the item ends
+    int item_rows;
+    bool cut;
+
+    // nb shares of q or q + 1 units (the first r are the longer ones)
+    __device__ void set_shares(long long total, int n) {
+        T = total; nb = n;
+        q = div_u(total, n);
+        r = (int)(total - q * n);
+    }
+    __device__ long long share_start(int bb) const { return bb * q + min(bb, r); }
+    __device__ int owner_of(long long upto) const {  // largest bb with share_start(bb) < upto; upto >= 1
+        const long long y = upto - 1, longer = (long long)r * (q + 1);
+        const int bb = y < longer ? (int)div_u(y, q + 1) : r + (int)div_u(y - longer, q);
+        return min(bb, nb - 1);
+    }
+    // Next segment of the share; false when the share is exhausted.
+    __device__ bool next(const FastArgs& a, Segment& sg) {
+        while (x < x1) {
+            const Item it = locate(pref, cost, a.B, a.H_kv, x);
+            const long long iend = it.base + (long long)it.nt * it.cost;
+            // tiles [it.tile, xt_e) of the item, phantom tiles included, are this workgroup's
+            const int xt_e = x1 >= iend ? it.nt : (int)div_u(x1 - it.base, it.cost);
+            const int nt = it.nt - seg_tiles, tile_a = max(it.tile - seg_tiles, 0), tile_e = max(xt_e - seg_tiles, 0);
+            // scalar loads (constant address space, uniform index): they must not queue behind the K/V
+            // tile loads that are in flight while the next segment is being looked up
+            const int ri = uniform(it.i);
+            const const_i32* cu = (const const_i32*)a.cu_q;
+            const const_i32* cx = (const const_i32*)a.ctx;
+            const int q0 = cu[ri], q_len = cu[ri + 1] - q0;
+            const int rows = a.G * q_len;
+            sg.i = ri; sg.kvh = uniform(it.g); sg.c = max((int)cx[ri], 0); sg.q0 = q0; sg.q_len = q_len;
+            first_end = it.base + (long long)(seg_tiles + 1) * it.cost; item_end = iend; item_rows = rows;
+            if (tile_e > tile_a) {
+                if (rows <= 16 * mt_max) {
+                    sg.j0 = 0; sg.rows_g = q_len; sg.tile_a = tile_a; sg.tile_e = tile_e;
+                    sg.final_out = tile_a == 0 && tile_e == nt;
+                    sg.slot = b * 2 + (tile_a > 0 ? 0 : 1);
+                    cut = !sg.final_out;
+                    x = x1 >= iend ? iend : x1;
+                    return true;
+                }
+                if (tile_a == 0) {
+                    // more rows than a partial slot holds: the workgroup owning the item's first tile
+                    // does the whole item, in passes over groups of rows; the other workgroups skip it
+                    const int rows_per_pass = (16 * mt_max) / a.G;
+                    if (pass_j0 < q_len) {
+                        sg.j0 = pass_j0; sg.rows_g = min(rows_per_pass, q_len - pass_j0); sg.tile_a = 0; sg.tile_e = nt;
+                        sg.final_out = true; sg.slot = 0;
+                        cut = false;
+                        pass_j0 += rows_per_pass;
+                        if (pass_j0 >= q_len) {
+                            pass_j0 = 0;
+                            x = x1 >= iend ? iend : x1;
+                        }
+                        return true;
+                    }
+                }
+            }
+            x = x1 >= iend ? iend : x1;
+        }
+        return false;
+    }
+};
+
 __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, KVTile& t, int ti) {
     const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
     KVStream st;
@@ -331,6 +424,10 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
     auto issue = [&](KVTile& t, int ti) { issue_tile(a, st, t, ti); };
     // The K/V stream does not depend on Q: start it before anything else of the segment.
+    // Two tiles in flight per wave.  (A third, where the registers would allow it, does not raise
+    // the rate: a compute unit draws only about twice its even share of the HBM bandwidth however
+    // much it keeps in flight.)
+    constexpr int kDepth = 2;
     KVTile ta, tb;
     if (nw > 0) {
         issue(ta, 0);
@@ -511,22 +608,21 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     bool redo = false;
     if (nw > 0) {
         f32x4 s[MT][2];
-        for (int t = 0; t < nw; t += 2) {
-            stage_and_scores(ta, kb0 + t * kStep, s);
+        // one tile: wait for it, stage V, scores; refill its registers with the tile kDepth
+        // further on (past the end: a harmless repeat of the last tile); softmax and P V
+        auto fast_tile = [&](KVTile& tl, int t) {
+            const bool real = t < nw;
+            if (real) stage_and_scores(tl, kb0 + t * kStep, s);
             __builtin_amdgcn_sched_barrier(0);
-            issue(ta, t + 2);
+            issue(tl, t + kDepth);
             __builtin_amdgcn_sched_barrier(0);
             if (seg_no == 0 && t < 24) FSR_STAMP(16 + 2 * t);
-            fast_softmax_pv(kb0 + t * kStep, s);
+            if (real) fast_softmax_pv(kb0 + t * kStep, s);
             if (seg_no == 0 && t < 24) FSR_STAMP(17 + 2 * t);
-            const bool second = t + 1 < nw;
-            if (second) stage_and_scores(tb, kb0 + (t + 1) * kStep, s);
-            __builtin_amdgcn_sched_barrier(0);
-            issue(tb, t + 3);
-            __builtin_amdgcn_sched_barrier(0);
-            if (seg_no == 0 && t < 24) FSR_STAMP(18 + 2 * t);
-            if (second) fast_softmax_pv(kb0 + (t + 1) * kStep, s);
-            if (seg_no == 0 && t < 24) FSR_STAMP(19 + 2 * t);
+        };
+        for (int t = 0; t < nw; t += kDepth) {
+            fast_tile(ta, t);
+            fast_tile(tb, t + 1);
         }
         redo = __builtin_amdgcn_ballot_w64(!lane_ok) != 0;
     }
@@ -705,53 +801,75 @@ __device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment
 }
 
 // Combine the pieces of an item that share boundaries cut: slot 1 of workgroup b_first (which holds
-// the item's first tile) and slot 0 of b_first+1 .. b_last.  Called by one whole workgroup.
+// the item's first tile) and slot 0 of b_first+1 .. b_last.  Called by one whole workgroup.  A thread
+// owns up to kE (row, 4 d) elements and has the loads of all of them, for two pieces at a time, in
+// flight together: the pieces come from the point of coherence, a long way off.
+template <int MTMAX>
 __device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int g, int q0, int M) {
-    constexpr int kBatch = 4;  // pieces whose loads are in flight together
-    for (int e = threadIdx.x; e < M * (kD / 4); e += kThreads) {
-        const int m = e / (kD / 4), d0 = (e % (kD / 4)) * 4;
-        float m_star = -INFINITY, l = 0.0f;
-        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int bb0 = b_first; bb0 <= b_last; bb0 += kBatch) {
-            float pm[kBatch], pl[kBatch];
-            f32x4 po[kBatch];
+    constexpr int kE = (16 * MTMAX * (kD / 4) + kThreads - 1) / kThreads;
+    constexpr int kBatch = 2;
+    const int n_elem = M * (kD / 4);
+    float m_star[kE], l[kE];
+    f32x4 o[kE];
+#pragma unroll
+    for (int e = 0; e < kE; ++e) {
+        m_star[e] = -INFINITY;
+        l[e] = 0.0f;
+        o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int bb0 = b_first; bb0 <= b_last; bb0 += kBatch) {
+        float pm[kE][kBatch], pl[kE][kBatch];
+        f32x4 po[kE][kBatch];
+#pragma unroll
+        for (int e = 0; e < kE; ++e) {
+            const int idx = min((int)threadIdx.x + e * kThreads, n_elem - 1);  // past the end: a valid element, unused
+            const int m = idx / (kD / 4), d0 = (idx % (kD / 4)) * 4;
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
                 const int bb = min(bb0 + k, b_last);  // past the end: the last piece again, weighted 0 below
                 const size_t row = (size_t)(bb * 2 + (bb == b_first ? 1 : 0)) * a.m_cap + m;
-                coherent_load2(a.part_ml + row * 2, pm[k], pl[k]);
-                po[k] = coherent_load4(a.part_o + row * kD + d0);
+                coherent_load2(a.part_ml + row * 2, pm[e][k], pl[e][k]);
+                po[e][k] = coherent_load4(a.part_o + row * kD + d0);
             }
-            float m_new = m_star;
+        }
+#pragma unroll
+        for (int e = 0; e < kE; ++e) {
+            float m_new = m_star[e];
 #pragma unroll
             for (int k = 0; k < kBatch; ++k)
-                if (bb0 + k <= b_last) m_new = fmaxf(m_new, pm[k]);
+                if (bb0 + k <= b_last) m_new = fmaxf(m_new, pm[e][k]);
             const float mu = m_new == -INFINITY ? 0.0f : m_new;
-            const float keep = fast_exp2(m_star - mu);  // 0 while nothing has been accumulated
-            l *= keep;
-            o *= keep;
+            const float keep = fast_exp2(m_star[e] - mu);  // 0 while nothing has been accumulated
+            l[e] *= keep;
+            o[e] *= keep;
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
-                const float wgt = bb0 + k <= b_last ? fast_exp2(pm[k] - mu) : 0.0f;
-                l += pl[k] * wgt;
-                o += po[k] * wgt;
+                const float wgt = bb0 + k <= b_last ? fast_exp2(pm[e][k] - mu) : 0.0f;
+                l[e] += pl[e][k] * wgt;
+                o[e] += po[e][k] * wgt;
             }
-            m_star = m_new;
+            m_star[e] = m_new;
         }
-        o *= 1.0f / l;
+    }
+#pragma unroll
+    for (int e = 0; e < kE; ++e) {
+        const int idx = threadIdx.x + e * kThreads;
+        if (idx >= n_elem) break;
+        const int m = idx / (kD / 4), d0 = (idx % (kD / 4)) * 4;
+        const f32x4 r = o[e] * (1.0f / l[e]);
         const int j = m / a.G, h = g * a.G + m % a.G;
         const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
         if (a.out_bf16) {
             ushort4 pk;
-            pk.x = f32_to_bf16_rne(o[0]);
-            pk.y = f32_to_bf16_rne(o[1]);
-            pk.z = f32_to_bf16_rne(o[2]);
-            pk.w = f32_to_bf16_rne(o[3]);
+            pk.x = f32_to_bf16_rne(r[0]);
+            pk.y = f32_to_bf16_rne(r[1]);
+            pk.z = f32_to_bf16_rne(r[2]);
+            pk.w = f32_to_bf16_rne(r[3]);
             *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(a.out) + o_idx) = pk;
         } else {
-            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + o_idx) = o;
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + o_idx) = r;
         }
-        if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (m_star + __log2f(l)) * kLn2;
+        if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (m_star[e] + __log2f(l[e])) * kLn2;
     }
 }
 
@@ -768,73 +886,9 @@ __device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned 
     }
 }
 
-// Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
-struct ShareWalker {
-    const long long* pref;
-    const unsigned char* cost;
-    long long x, x1, T;
-    int nb, b, mt_max, pass_j0;
-    // what the segment just handed out is part of (for counting the pieces of a cut item)
-    long long item_base, item_end;
-    int item_cost, item_rows;
-    bool cut;
-
-    __device__ long long share_start(int bb) const { return (long long)bb * T / nb; }
-    __device__ int owner_of(long long upto) const {  // largest bb with share_start(bb) < upto
-        int bb = (int)((upto - 1) * nb / T);
-        while (bb + 1 < nb && share_start(bb + 1) < upto) ++bb;
-        while (bb > 0 && share_start(bb) >= upto) --bb;
-        return bb;
-    }
-    // Next segment of the share; false when the share is exhausted.
-    __device__ bool next(const FastArgs& a, Segment& sg) {
-        while (x < x1) {
-            const Item it = locate(pref, cost, a.B, a.H_kv, x);
-            const long long iend = it.base + (long long)it.nt * it.cost;
-            const int tile_e = x1 >= iend ? it.nt : (int)((x1 - it.base) / it.cost);
-            // scalar loads (constant address space, uniform index): they must not queue behind the K/V
-            // tile loads that are in flight while the next segment is being looked up
-            const int ri = uniform(it.i);
-            const const_i32* cu = (const const_i32*)a.cu_q;
-            const const_i32* cx = (const const_i32*)a.ctx;
-            const int q0 = cu[ri], q_len = cu[ri + 1] - q0;
-            const int rows = a.G * q_len;
-            sg.i = ri; sg.kvh = uniform(it.g); sg.c = max((int)cx[ri], 0); sg.q0 = q0; sg.q_len = q_len;
-            item_base = it.base; item_end = iend; item_cost = it.cost; item_rows = rows;
-            if (tile_e > it.tile) {
-                if (rows <= 16 * mt_max) {
-                    sg.j0 = 0; sg.rows_g = q_len; sg.tile_a = it.tile; sg.tile_e = tile_e;
-                    sg.final_out = it.tile == 0 && tile_e == it.nt;
-                    sg.slot = b * 2 + (it.tile > 0 ? 0 : 1);
-                    cut = !sg.final_out;
-                    x = x1 >= iend ? iend : x1;
-                    return true;
-                }
-                if (it.tile == 0) {
-                    // more rows than a partial slot holds: the workgroup owning the item's first tile
-                    // does the whole item, in passes over groups of rows; the other workgroups skip it
-                    const int rows_per_pass = (16 * mt_max) / a.G;
-                    if (pass_j0 < q_len) {
-                        sg.j0 = pass_j0; sg.rows_g = min(rows_per_pass, q_len - pass_j0); sg.tile_a = 0; sg.tile_e = it.nt;
-                        sg.final_out = true; sg.slot = 0;
-                        cut = false;
-                        pass_j0 += rows_per_pass;
-                        if (pass_j0 >= q_len) {
-                            pass_j0 = 0;
-                            x = x1 >= iend ? iend : x1;
-                        }
-                        return true;
-                    }
-                }
-            }
-            x = x1 >= iend ? iend : x1;
-        }
-        return false;
-    }
-};
-
-// Persistent grid: nb workgroups of 256 threads; workgroup b takes the share
-// [b T / nb', (b+1) T / nb') of the cost line, nb' = min(nb, T / dearest tile).  An item that lies
+// Persistent grid: nb workgroups of 256 threads; the cost line [0, T) is cut into nb' = min(nb,
+// T / dearest tile) shares whose lengths differ by at most one unit, workgroup b takes share b.  A
+// workgroup owns the tiles that END inside its share (phantom tiles are owned and skipped).  An item that lies
 // inside one share is finished by that workgroup; an item cut by share boundaries leaves one
 // partial per piece, and the workgroup whose piece arrives last combines them (no workgroup ever
 // waits for another).
@@ -852,10 +906,15 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     FSR_STAMP(1);
     ShareWalker wk;
     wk.pref = pref; wk.cost = cost;
-    wk.T = pref[a.B] * a.H_kv;
-    // every share is at least as wide as the dearest tile, so every workgroup owns at least one tile
-    wk.nb = (int)min((long long)a.nb, wk.T / cmax);
-    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.pass_j0 = 0; wk.cut = false;
+    {
+        // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
+        // item then owns at least one of its tiles
+        const long long total = pref[a.B] * a.H_kv;
+        const int nbx = (int)min((long long)a.nb, div_u(total, cmax));
+        if ((int)blockIdx.x >= nbx) return;
+        wk.set_shares(total, nbx);
+    }
+    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.pass_j0 = 0; wk.cut = false; wk.seg_tiles = a.seg_tiles;
     if (wk.b >= wk.nb) return;
     wk.x = wk.share_start(wk.b);
     wk.x1 = wk.share_start(wk.b + 1);
@@ -869,7 +928,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
         if (wk.cut) {
             // pieces of this item: the workgroups that own its first .. last tile; workgroup bb owns
             // tile k iff share_start(bb) < base + (k + 1) * cost <= share_start(bb + 1)
-            const int b_first = wk.owner_of(wk.item_base + wk.item_cost), b_last = wk.owner_of(wk.item_end);
+            const int b_first = wk.owner_of(wk.first_end), b_last = wk.owner_of(wk.item_end);
             // the piece's stores are device-coherent; once every wave has seen them acknowledged the
             // piece may be counted
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -878,7 +937,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
             __syncthreads();
             FSR_STAMP(100 + min(seg_no - 1, 1) * 2);
             if (s_last) {
-                combine_cut_item(a, b_first, b_last, cur.kvh, cur.q0, wk.item_rows);
+                combine_cut_item<MTMAX>(a, b_first, b_last, cur.kvh, cur.q0, wk.item_rows);
                 if (threadIdx.x == 0) __atomic_store_n(a.arrivals + b_first + 1, a.call_id << 16, __ATOMIC_RELAXED);
             }
             __syncthreads();
@@ -1089,6 +1148,8 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
         a.max_pages = p->max_pages; a.n_pages = p->n_pages;
         a.nb = pl.nb; a.m_cap = 16 * pl.mt_max; a.out_bf16 = p->out_dtype == FSR_BF16;
         a.scale_log2 = p->scale * kLog2e;
+        a.seg_tiles = kSegTiles;
+        a.cost_base = kCostBase;
 #ifdef FSR_TIMING
         a.dbg = (long long*)((char*)workspace + need);  // the timing build expects 1 MiB of slack after the workspace
 #endif
