@@ -77,3 +77,35 @@ def check_accept(gpu, ref, u_sample):
         n = ref["accepted_len"][i]
         assert np.array_equal(em[i, :n], ref["emitted"][i, :n])
     return int(frag.sum()), len(diff_rows)
+
+
+def chunked_case(fsr, oracle, b, chunks, dtype):
+    """Frontier verification of batch ``b`` through the C ABI against the chunked oracle and the
+    one-shot accept: lengths bit-exact, tokens bit-exact except fragile draws, exactly the same rows
+    computed, attention rows within tolerance, same number of rows processed."""
+    ref = oracle.verify_chunked(b, chunks)
+    one = oracle.spec_accept(b.p_target, b.p_draft, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d,
+                             S_max=b.S_max)
+    assert np.array_equal(ref["emitted"], one["emitted"])
+    d = DeviceBatch(b)
+    out = torch.full(d.q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    r = fsr.verify_chunked(q=d.q, k_caches=[d.k_cache], v_caches=[d.v_cache], block_tables=d.block_tables,
+                           ctx_lens=d.ctx_lens, spec_lens=d.spec_lens, cu_q=d.cu_q, cu_d=d.cu_d, p_target=d.p_target,
+                           p_draft=d.p_draft, draft_tokens=d.draft_tokens, u_accept=d.u_accept, u_sample=d.u_sample,
+                           chunks=[dev(c) for c in chunks], scale=b.scale, S_total_max=b.S_max,
+                           chunk_S_max=int(max(c.max() for c in chunks)), out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(r["accepted_len"].cpu().numpy(), ref["accepted_len"])
+    assert np.array_equal(r["n_emitted"].cpu().numpy(), ref["n_emitted"])
+    em = r["emitted"].cpu().numpy()
+    frag = fragile_draws(b.u_sample, one["cdf_lo"], one["cdf_hi"])
+    for i in np.where((em != ref["emitted"]).any(axis=1))[0]:
+        assert frag[i], (i, em[i], ref["emitted"][i])
+    o = out.cpu().numpy()
+    done_ref = ~np.isnan(ref["out"][:, 0, 0])
+    done_gpu = ~np.isnan(o[:, 0, 0])
+    assert np.array_equal(done_ref, done_gpu)          # exactly the same rows were computed
+    rows = np.where(done_ref)[0]
+    err = check_attention(out[torch.from_numpy(rows).cuda()], ref["out"][rows], dtype, len(rows))
+    assert sum(int(x.item()) for x in r["rows"]) == ref["rows_processed"]
+    return dict(err=err, rows=len(rows), rows_total=b.N, fragile=int(frag.sum()), accepted=int(ref["accepted_len"].sum()))

@@ -13,8 +13,10 @@ cache of a continuous-batching engine, Sec. 2.1) are mirrored.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 import math
+import os
 from typing import Optional
 
 import numpy as np
@@ -42,15 +44,33 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def _normal_store(rng: np.random.Generator, shape, dtype: str, chunk: int = 1 << 24) -> np.ndarray:
-    """N(0,1) values in the storage format: fp32, or bf16 bit patterns (uint16)."""
+def _workers() -> int:
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def _parallel_chunks(rng: np.random.Generator, n: int, chunk: int, fill) -> None:
+    """Call fill(child_rng, a, b) for the chunks [a, b) of range(n), each chunk with its own child
+    generator spawned from ``rng`` (so the result does not depend on the number of threads)."""
+    starts = list(range(0, n, chunk))
+    kids = rng.spawn(len(starts))
+    with concurrent.futures.ThreadPoolExecutor(_workers()) as ex:
+        list(ex.map(lambda t: fill(t[0], t[1], min(n, t[1] + chunk)), zip(kids, starts)))
+
+
+def _normal_store(rng: np.random.Generator, shape, dtype: str, chunk: int = 1 << 22) -> np.ndarray:
+    """N(0,1) values in the storage format: fp32, or bf16 bit patterns (uint16).  Arrays larger than
+    one chunk are filled chunk by chunk from child generators, several chunks at a time."""
     n = int(np.prod(shape))
-    if dtype == "f32":
-        return rng.standard_normal(n, dtype=np.float32).reshape(shape)
-    out = np.empty(n, dtype=np.uint16)
-    for a in range(0, n, chunk):
-        b = min(n, a + chunk)
-        out[a:b] = f32_to_bf16_bits(rng.standard_normal(b - a, dtype=np.float32))
+    if n <= chunk:
+        x = rng.standard_normal(n, dtype=np.float32)
+        return (x if dtype == "f32" else f32_to_bf16_bits(x)).reshape(shape)
+    out = np.empty(n, dtype=np.float32 if dtype == "f32" else np.uint16)
+
+    def fill(child, a, b):
+        x = child.standard_normal(b - a, dtype=np.float32)
+        out[a:b] = x if dtype == "f32" else f32_to_bf16_bits(x)
+
+    _parallel_chunks(rng, n, chunk, fill)
     return out.reshape(shape)
 
 
@@ -162,13 +182,17 @@ def build_paged_kv(rng, ctx_lens, q_lens, H_kv, D, P, dtype, spare_pages=3, perm
 def softmax_rows_f32(z: np.ndarray, temperature: float = 1.0) -> np.ndarray:
     """fp64 softmax of logits, rounded to fp32: how the synthetic probability inputs are made."""
     out = np.empty(z.shape, dtype=np.float32)
-    step = max(1, (1 << 22) // max(1, z.shape[1]))
-    for a in range(0, z.shape[0], step):
+    step = max(1, (1 << 21) // max(1, z.shape[1]))
+
+    def block(a):
         x = z[a : a + step].astype(np.float64) / temperature
         x -= x.max(axis=1, keepdims=True)
         np.exp(x, out=x)
         x /= x.sum(axis=1, keepdims=True)
         out[a : a + step] = x
+
+    with concurrent.futures.ThreadPoolExecutor(_workers()) as ex:
+        list(ex.map(block, range(0, z.shape[0], step)))
     return out
 
 
@@ -176,9 +200,13 @@ def sample_rows(rng, p: np.ndarray) -> np.ndarray:
     """One token per row, drawn from the row's distribution (the draft model's own sampling)."""
     tok = np.empty(p.shape[0], dtype=np.int32)
     u = rng.random(p.shape[0])
-    for r in range(p.shape[0]):
+
+    def one(r):
         c = np.cumsum(p[r].astype(np.float64))
         tok[r] = min(int(np.searchsorted(c, u[r] * c[-1], side="right")), p.shape[1] - 1)
+
+    with concurrent.futures.ThreadPoolExecutor(_workers()) as ex:
+        list(ex.map(one, range(p.shape[0])))
     return tok
 
 
