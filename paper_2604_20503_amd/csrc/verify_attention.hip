@@ -47,7 +47,7 @@ constexpr int kP = 16;            // page size of the fast path
 constexpr int kTile = 32;         // keys per wave tile
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-constexpr int kMaxMT = 6;         // up to 96 query rows (G * rows) per pass
+constexpr int kMaxMT = 4;         // up to 64 query rows (G * suffix positions) per row group
 constexpr int kMaxB = 4096;       // requests whose tile prefix fits the LDS table
 constexpr int kRedStride = kD + 4;  // padded row of the wave-merge buffer (floats)
 // LDS map: [V tiles of the 4 waves | wave-merge buffer] (shared region), wave maxima and sums,
@@ -61,9 +61,7 @@ constexpr int kQOff = kMlOff + kMlBytes;          // Q^T operands of the current
 constexpr int kQBytes = kMaxMT * 4 * 64 * 16;
 constexpr int kPrefOff = kQOff + kQBytes;
 constexpr int kPrefBytes = (kMaxB + 1) * 8;          // weighted tile prefix (64-bit)
-constexpr int kCostOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
-constexpr int kCostBytes = ((kMaxB + 15) / 16) * 16;  // per-request cost of one tile (bytes)
-constexpr int kScanOff = kCostOff + kCostBytes;
+constexpr int kScanOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
 constexpr int kFastSmem = kScanOff + 64;
 constexpr int kCostBase = 1;  // a tile costs kCostBase + (16-row query tiles riding on it)
 constexpr int kSegTiles = 8;  // what starting an item costs a workgroup (merge, refill), in tiles of that item
@@ -130,26 +128,38 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) { return __builtin_
 __device__ __forceinline__ int vtile_off(int key, int ch) { return key * 256 + ((ch ^ ((key & 7) << 1)) << 4); }
 
 // ---------------------------------------------------------------------------------------
-// Schedule.  Work is measured in cost units: a 32-key tile of request i costs cost[i] units,
-// more when more query-row tiles ride on it (1 + number of 16-row tiles), so that shares of
-// equal cost take about equal time whether a request has one suffix row or nine.
-// In front of its real tiles every item carries seg_tiles phantom tiles: they stand for what it
-// costs a workgroup to take up an item at all (merging its waves, refilling the load pipeline),
-// so a workgroup whose share spans an item boundary is handed fewer real tiles than one that
-// streams a single item throughout.
-// pref[i] = cost of the tiles of requests 0..i-1 for one KV head; item (i, g) with nt_i tiles
-// (phantom ones included) owns the flattened cost interval
-// [pref[i] * H_kv + g * nt_i * cost[i], ... + nt_i * cost[i]).
+// Schedule.  An item is (request i, KV head g, row group k): the rows of request i that share KV
+// head g, in groups of at most 16 * mt_max rows (whole suffix positions: rows_per_group = 16 *
+// mt_max / G positions), so that a group's accumulators fit the kernel's registers.  Nearly always
+// a request is one group.  Work is measured in cost units: a 32-key tile of a group costs
+// cost_base + (16-row query tiles riding on it), so that shares of equal cost take about equal
+// time whether a request has one suffix row or nine.  In front of its real tiles every item carries
+// seg_tiles phantom tiles: they stand for what it costs a workgroup to take up an item at all
+// (merging its waves, refilling the load pipeline), so a workgroup whose share spans an item
+// boundary is handed fewer real tiles than one that streams a single item throughout.
+// pref[i] = cost of the items of requests 0..i-1 for one KV head; on the flattened cost line the
+// request's items follow each other head by head, and inside a head group by group.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int tile_cost(int rows_sharing_kv, int mt_max, int base) {
-    const int mt = (rows_sharing_kv + 15) >> 4;
-    if (mt <= mt_max) return base + mt;
-    const int passes = (mt + mt_max - 1) / mt_max;  // such an item is done in passes by one workgroup
-    return min(passes * (base + mt_max), 255);
-}
+struct Group {
+    int j0, rows_g;  // suffix positions j0 .. j0 + rows_g - 1 of the request
+    int nt, cost;    // tiles (phantom ones included) and cost of one tile
+};
 
-// Returns the largest per-tile cost of any request.
-__device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, unsigned char* cost, long long* scratch) {
+// Group of request (context c, q_len rows) that starts at suffix position j0.
+__device__ __forceinline__ Group group_at(const FastArgs& a, int mt_max, int c, int q_len, int j0) {
+    const int per_group = max((16 * mt_max) / a.G, 1);
+    Group gr;
+    gr.j0 = j0;
+    gr.rows_g = min(per_group, q_len - j0);
+    const int visible = min(c + j0 + gr.rows_g, a.max_pages * kP);  // keys the group's last row sees
+    gr.nt = (visible + kTile - 1) / kTile + a.seg_tiles;
+    gr.cost = a.cost_base + min((a.G * gr.rows_g + 15) >> 4, mt_max);
+    return gr;
+}
+__device__ __forceinline__ int rows_per_group(const FastArgs& a, int mt_max) { return max((16 * mt_max) / a.G, 1); }
+
+// Returns the largest per-tile cost of any item.
+__device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, long long* scratch) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     long long carry = 0;
     int cmax = 1;
@@ -157,15 +167,12 @@ __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref,
         const int i = base + threadIdx.x;
         long long units = 0;
         if (i < a.B) {
-            const int ql = a.cu_q[i + 1] - a.cu_q[i];
-            int cst = 1;
-            if (ql > 0) {
-                const int L = min(max(a.ctx[i], 0) + ql, a.max_pages * kP);
-                cst = tile_cost(a.G * ql, mt_max, a.cost_base);
-                units = (long long)((L + kTile - 1) / kTile + a.seg_tiles) * cst;
+            const int ql = a.cu_q[i + 1] - a.cu_q[i], c = max(a.ctx[i], 0);
+            for (int j0 = 0; j0 < ql; j0 += rows_per_group(a, mt_max)) {
+                const Group gr = group_at(a, mt_max, c, ql, j0);
+                units += (long long)gr.nt * gr.cost;
+                cmax = max(cmax, gr.cost);
             }
-            cost[i] = (unsigned char)cst;
-            cmax = max(cmax, cst);
         }
         const long long inc = wave_inclusive_scan(units);
         if (lane == 63) scratch[w] = inc;
@@ -189,12 +196,6 @@ __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref,
     return cmax;
 }
 
-struct Item {
-    int i, g, nt, cost, tile;  // request, KV head, tiles of the item and the position's tile (both counting the
-                               // phantom tiles in front), cost of one tile
-    long long base;            // flattened cost position of the item's first (phantom) tile
-};
-
 // Quotient of two non-negative numbers; nearly always both fit 32 bits, where the division is an
 // order of magnitude cheaper than the 64-bit one.
 __device__ __forceinline__ long long div_u(long long n, long long d) {
@@ -202,22 +203,14 @@ __device__ __forceinline__ long long div_u(long long n, long long d) {
     return n / d;
 }
 
-__device__ __forceinline__ Item locate(const long long* pref, const unsigned char* cost, int B, int H_kv, long long x) {
-    int lo = 0, hi = B;  // largest i with pref[i] * H_kv <= x
+// Request whose items hold cost position x: largest i with pref[i] * H_kv <= x.
+__device__ __forceinline__ int locate_request(const long long* pref, int B, int H_kv, long long x) {
+    int lo = 0, hi = B;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (pref[mid] * H_kv <= x) lo = mid; else hi = mid;
     }
-    Item it;
-    it.i = lo;
-    it.cost = cost[lo];
-    const long long item_units = pref[lo + 1] - pref[lo];
-    it.nt = (int)div_u(item_units, it.cost);
-    const long long local = x - pref[lo] * H_kv;
-    it.g = (int)div_u(local, item_units);
-    it.base = pref[lo] * H_kv + it.g * item_units;
-    it.tile = (int)div_u(x - it.base, it.cost);
-    return it;
+    return lo;
 }
 
 struct KVTile {
@@ -274,7 +267,7 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
     st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
     const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
-    // keys any row of this pass may see
+    // keys any row of this group may see
     st.kend = min(min(__builtin_amdgcn_readfirstlane(sg.tile_e) * kTile,
                       c + __builtin_amdgcn_readfirstlane(sg.j0) + __builtin_amdgcn_readfirstlane(sg.rows_g)), st.kv_total);
     st.kb0 = kbeg + w * kTile;
@@ -289,9 +282,8 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
 // Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
 struct ShareWalker {
     const long long* pref;
-    const unsigned char* cost;
     long long x, x1, T, q;
-    int nb, r, b, mt_max, pass_j0, seg_tiles;
+    int nb, r, b, mt_max;
     // what the segment just handed out is part of (for counting the pieces of a cut item)
     long long first_end, item_end;  // cost position where the item's first real tile ends / the item ends
     int item_rows;
@@ -312,47 +304,36 @@ struct ShareWalker {
     // Next segment of the share; false when the share is exhausted.
     __device__ bool next(const FastArgs& a, Segment& sg) {
         while (x < x1) {
-            const Item it = locate(pref, cost, a.B, a.H_kv, x);
-            const long long iend = it.base + (long long)it.nt * it.cost;
-            // tiles [it.tile, xt_e) of the item, phantom tiles included, are this workgroup's
-            const int xt_e = x1 >= iend ? it.nt : (int)div_u(x1 - it.base, it.cost);
-            const int nt = it.nt - seg_tiles, tile_a = max(it.tile - seg_tiles, 0), tile_e = max(xt_e - seg_tiles, 0);
             // scalar loads (constant address space, uniform index): they must not queue behind the K/V
             // tile loads that are in flight while the next segment is being looked up
-            const int ri = uniform(it.i);
+            const int ri = uniform(locate_request(pref, a.B, a.H_kv, x));
             const const_i32* cu = (const const_i32*)a.cu_q;
             const const_i32* cx = (const const_i32*)a.ctx;
-            const int q0 = cu[ri], q_len = cu[ri + 1] - q0;
-            const int rows = a.G * q_len;
-            sg.i = ri; sg.kvh = uniform(it.g); sg.c = max((int)cx[ri], 0); sg.q0 = q0; sg.q_len = q_len;
-            first_end = it.base + (long long)(seg_tiles + 1) * it.cost; item_end = iend; item_rows = rows;
-            if (tile_e > tile_a) {
-                if (rows <= 16 * mt_max) {
-                    sg.j0 = 0; sg.rows_g = q_len; sg.tile_a = tile_a; sg.tile_e = tile_e;
-                    sg.final_out = tile_a == 0 && tile_e == nt;
-                    sg.slot = b * 2 + (tile_a > 0 ? 0 : 1);
-                    cut = !sg.final_out;
-                    x = x1 >= iend ? iend : x1;
-                    return true;
-                }
-                if (tile_a == 0) {
-                    // more rows than a partial slot holds: the workgroup owning the item's first tile
-                    // does the whole item, in passes over groups of rows; the other workgroups skip it
-                    const int rows_per_pass = (16 * mt_max) / a.G;
-                    if (pass_j0 < q_len) {
-                        sg.j0 = pass_j0; sg.rows_g = min(rows_per_pass, q_len - pass_j0); sg.tile_a = 0; sg.tile_e = nt;
-                        sg.final_out = true; sg.slot = 0;
-                        cut = false;
-                        pass_j0 += rows_per_pass;
-                        if (pass_j0 >= q_len) {
-                            pass_j0 = 0;
-                            x = x1 >= iend ? iend : x1;
-                        }
-                        return true;
-                    }
-                }
+            const int q0 = cu[ri], q_len = cu[ri + 1] - q0, c = max((int)cx[ri], 0);
+            // the KV head, then the row group, that hold position x
+            const long long per_head = pref[ri + 1] - pref[ri], req_base = pref[ri] * a.H_kv;
+            const int g = (int)div_u(x - req_base, per_head);
+            long long base = req_base + g * per_head;
+            Group gr = group_at(a, mt_max, c, q_len, 0);
+            while (x >= base + (long long)gr.nt * gr.cost && gr.j0 + gr.rows_g < q_len) {
+                base += (long long)gr.nt * gr.cost;
+                gr = group_at(a, mt_max, c, q_len, gr.j0 + gr.rows_g);
             }
+            const long long iend = base + (long long)gr.nt * gr.cost;
+            // tiles [xt_a, xt_e) of the item, phantom tiles included, are this workgroup's
+            const int xt_a = (int)div_u(x - base, gr.cost);
+            const int xt_e = x1 >= iend ? gr.nt : (int)div_u(x1 - base, gr.cost);
+            const int nt = gr.nt - a.seg_tiles, tile_a = max(xt_a - a.seg_tiles, 0), tile_e = max(xt_e - a.seg_tiles, 0);
             x = x1 >= iend ? iend : x1;
+            if (tile_e > tile_a) {
+                sg.i = ri; sg.kvh = uniform(g); sg.c = c; sg.q0 = q0; sg.q_len = q_len;
+                sg.j0 = gr.j0; sg.rows_g = gr.rows_g; sg.tile_a = tile_a; sg.tile_e = tile_e;
+                sg.final_out = tile_a == 0 && tile_e == nt;
+                sg.slot = b * 2 + (tile_a > 0 ? 0 : 1);
+                first_end = base + (long long)(a.seg_tiles + 1) * gr.cost; item_end = iend; item_rows = a.G * gr.rows_g;
+                cut = !sg.final_out;
+                return true;
+            }
         }
         return false;
     }
@@ -792,10 +773,9 @@ __device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment
         if (mt == 1) FSR_SEG(1); else FSR_SEG(2);
     } else if constexpr (MTMAX == 3) {
         if (mt == 1) FSR_SEG(1); else if (mt == 2) FSR_SEG(2); else FSR_SEG(3);
-    } else if constexpr (MTMAX == 4) {
-        if (mt <= 2) FSR_SEG(2); else if (mt == 3) FSR_SEG(3); else FSR_SEG(4);
     } else {
-        if (mt <= 2) FSR_SEG(2); else if (mt <= 4) FSR_SEG(4); else FSR_SEG(6);
+        static_assert(MTMAX == 4, "kernels are built for 1 to 4 query tiles");
+        if (mt <= 2) FSR_SEG(2); else if (mt == 3) FSR_SEG(3); else FSR_SEG(4);
     }
 #undef FSR_SEG
 }
@@ -803,7 +783,8 @@ __device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment
 // Combine the pieces of an item that share boundaries cut: slot 1 of workgroup b_first (which holds
 // the item's first tile) and slot 0 of b_first+1 .. b_last.  Called by one whole workgroup.  A thread
 // owns up to kE (row, 4 d) elements and has the loads of all of them, for two pieces at a time, in
-// flight together: the pieces come from the point of coherence, a long way off.
+// flight together: the pieces come from the point of coherence, a long way off.  q0 = output row of
+// the item's first suffix position.
 template <int MTMAX>
 __device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int g, int q0, int M) {
     constexpr int kE = (16 * MTMAX * (kD / 4) + kThreads - 1) / kThreads;
@@ -897,15 +878,14 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
     long long* pref = reinterpret_cast<long long*>(smem + kPrefOff);
-    unsigned char* cost = reinterpret_cast<unsigned char*>(smem + kCostOff);
     FSR_STAMP(0);
 #ifdef FSR_TIMING
     if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 126 * 4] = clock64();
 #endif
-    const int cmax = build_cost_prefix(a, MTMAX, pref, cost, reinterpret_cast<long long*>(smem + kScanOff));
+    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + kScanOff));
     FSR_STAMP(1);
     ShareWalker wk;
-    wk.pref = pref; wk.cost = cost;
+    wk.pref = pref;
     {
         // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
         // item then owns at least one of its tiles
@@ -914,7 +894,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
         if ((int)blockIdx.x >= nbx) return;
         wk.set_shares(total, nbx);
     }
-    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.pass_j0 = 0; wk.cut = false; wk.seg_tiles = a.seg_tiles;
+    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.cut = false;
     if (wk.b >= wk.nb) return;
     wk.x = wk.share_start(wk.b);
     wk.x1 = wk.share_start(wk.b + 1);
@@ -937,7 +917,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
             __syncthreads();
             FSR_STAMP(100 + min(seg_no - 1, 1) * 2);
             if (s_last) {
-                combine_cut_item<MTMAX>(a, b_first, b_last, cur.kvh, cur.q0, wk.item_rows);
+                combine_cut_item<MTMAX>(a, b_first, b_last, cur.kvh, cur.q0 + cur.j0, wk.item_rows);
                 if (threadIdx.x == 0) __atomic_store_n(a.arrivals + b_first + 1, a.call_id << 16, __ATOMIC_RELAXED);
             }
             __syncthreads();
@@ -1039,7 +1019,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(GenericArgs a) {
 
 struct Plan {
     bool fast;
-    int mt_max;  // 16-row query tiles per pass of the fast kernel
+    int mt_max;  // 16-row query tiles per row group (template argument of the kernel)
     int nb;      // workgroups of the persistent grid
     size_t bytes_o, bytes_ml, bytes_cnt;
 };
@@ -1093,9 +1073,12 @@ Plan make_plan(const fsr_attn_params& p) {
     pl.fast = p.dtype == FSR_BF16 && p.D == kD && p.P == kP && G <= 16 && p.B <= kMaxB;
     if (!pl.fast) return pl;
     // rows of one request that share a KV head: G * max_q_len (unknown bound -> the widest kernel)
-    const long long m_rows = p.max_q_len > 0 ? (long long)G * p.max_q_len : 16 * kMaxMT;
-    const int mt = (int)std::min<long long>((m_rows + 15) / 16, kMaxMT);
-    pl.mt_max = mt <= 4 ? mt : kMaxMT;
+    // When they fit four query tiles they are one row group; beyond that (or with no bound given) a
+    // request is cut into row groups of up to three tiles, the widest kernel that keeps its
+    // accumulators and both K/V tiles in registers without spilling.
+    const long long m_rows = p.max_q_len > 0 ? (long long)G * p.max_q_len : 1 << 20;
+    const long long mt = (m_rows + 15) / 16;
+    pl.mt_max = mt <= kMaxMT ? (int)mt : 3;
     // the workspace is sized for up to 1024 workgroups so that its size does not depend on the device
     pl.nb = std::min(persistent_blocks(), 1024);
     pl.bytes_o = align_up((size_t)1024 * 2 * 16 * pl.mt_max * kD * sizeof(float), 256);
@@ -1158,8 +1141,7 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
             case 1: hipLaunchKernelGGL(attn_stream_kernel<1>, grid, block, kFastSmem, s, a); break;
             case 2: hipLaunchKernelGGL(attn_stream_kernel<2>, grid, block, kFastSmem, s, a); break;
             case 3: hipLaunchKernelGGL(attn_stream_kernel<3>, grid, block, kFastSmem, s, a); break;
-            case 4: hipLaunchKernelGGL(attn_stream_kernel<4>, grid, block, kFastSmem, s, a); break;
-            default: hipLaunchKernelGGL(attn_stream_kernel<6>, grid, block, kFastSmem, s, a); break;
+            default: hipLaunchKernelGGL(attn_stream_kernel<4>, grid, block, kFastSmem, s, a); break;
         }
         return check_launch("attn_stream_kernel");
     }
