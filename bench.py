@@ -9,6 +9,9 @@ step's target/draft distributions (vocabulary 128256), then ``survivor_mask`` +
 timed region; the 32 layers use 32 distinct caches (5 GB) so the reads come from HBM and not
 from the last-level cache.  The step is captured once into a HIP graph and replayed.
 
+``--workload 3|4|5`` runs the same one-shot step at the batch shapes of the other configurations
+(their layers cycle through as many distinct caches as fit 16 GB); the metric is quoted on the default.
+
 Prints ONE JSON line: verified draft tokens/s (sum of the speculative lengths submitted per
 step / step time), the HBM roofline of the dominant kernel (attention), and the CPU oracle
 timed beside it on the host cores.
@@ -29,11 +32,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 N_LAYERS = 32           # Llama-3-8B depth: attention calls per verification step
+WORKLOADS = {
+    2: "cfg2 llama3_8b_layer: B=16, 32 q / 8 kv heads, D=128, bf16 paged KV (page 16, permuted), "
+       "ctx U[1024,4096], spec U[1,8], vocab 128256",
+    3: "cfg3 high_load: B=128, 32 q / 8 kv heads, D=128, bf16 paged KV, ctx lognormal(median 2048) <= 8192, "
+       "spec geometric 0..7, vocab 128256",
+    4: "cfg4 70b_share, one-shot: B=256, 64 q / 8 kv heads, D=128, bf16 paged KV, ctx lognormal(median 2048) in "
+       "[16,16384], spec U[1,10], vocab 128256",
+    5: "cfg5 chunked_frontier shapes, one-shot: B=512, 32 q / 8 kv heads, D=128, bf16 paged KV, ctx U[512,8192], "
+       "spec U[2,8], vocab 152064",
+}
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
 
 
-def build_step(fsr, torch, b, n_layers, seed):
-    """Device buffers and a closure running one full step without allocating."""
+def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9):
+    """Device buffers and a closure running one full step without allocating.  The layers cycle
+    through as many distinct KV caches as fit the budget (all 32 at workload 2)."""
     def dev(x, bf16=False):
         t = torch.from_numpy(np.ascontiguousarray(x.view(np.int16) if bf16 else x)).cuda()
         return t.view(torch.bfloat16) if bf16 else t
@@ -43,9 +57,20 @@ def build_step(fsr, torch, b, n_layers, seed):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     k_caches, v_caches = [k0], [v0]
-    for _ in range(1, n_layers):  # other layers: same shape and distribution, drawn on the device
-        k_caches.append(torch.randn(k0.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
-        v_caches.append(torch.randn(v0.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
+    kv_bytes = 2 * k0.numel() * k0.element_size()
+    n_caches = int(max(1, min(n_layers, cache_budget_bytes // kv_bytes)))
+
+    def draw_like(t):  # other layers: same shape and distribution, drawn on the device in slabs
+        o = torch.empty_like(t)
+        flat = o.view(-1)
+        for a in range(0, flat.numel(), 1 << 28):
+            n = min(1 << 28, flat.numel() - a)
+            flat[a:a + n] = torch.randn(n, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        return o
+
+    for _ in range(1, n_caches):
+        k_caches.append(draw_like(k0))
+        v_caches.append(draw_like(v0))
     bt, ctx, spec, cu_q, cu_d = dev(b.block_tables), dev(b.ctx_lens), dev(b.spec_lens), dev(b.cu_q), dev(b.cu_d)
     p_t, p_d = dev(b.p_target), dev(b.p_draft)
     toks, u_a, u_s = dev(b.draft_tokens), dev(b.u_accept), dev(b.u_sample)
@@ -67,8 +92,8 @@ def build_step(fsr, torch, b, n_layers, seed):
 
     def attention_all_layers():
         for l in range(n_layers):
-            fsr.verify_attention(q, k_caches[l], v_caches[l], bt, ctx, spec, cu_q, scale=b.scale, out=out,
-                                 workspace=ws_attn, max_q_len=S_max + 1)
+            fsr.verify_attention(q, k_caches[l % n_caches], v_caches[l % n_caches], bt, ctx, spec, cu_q, scale=b.scale,
+                                 out=out, workspace=ws_attn, max_q_len=S_max + 1)
 
     def tail():
         fsr.spec_accept(p_t, p_d, toks, u_a, u_s, cu_q, cu_d, S_max=S_max, accepted_len=acc, n_emitted=nem, emitted=em,
@@ -80,7 +105,8 @@ def build_step(fsr, torch, b, n_layers, seed):
         attention_all_layers()
         tail()
 
-    state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed)
+    state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed,
+                 n_caches=n_caches, kv_bytes=kv_bytes)
     return step, attention_all_layers, tail, state
 
 
@@ -109,10 +135,10 @@ def cpu_baseline(b, n_layers):
                        f"compaction ({t_pr * 1e3:.2f} ms) at full size"), r
 
 
-def measured_traffic():
+def measured_traffic(workload):
     """HBM bytes per attention launch from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE, scaled by a plain copy of known size), or None if there is no summary."""
-    path = os.path.join(ROOT, "profiles", "attn_stream_kernel_cfg2_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"attn_stream_kernel_cfg{workload}_hbm_traffic.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -128,6 +154,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=N_LAYERS)
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5],
+                    help="workload configuration; 2 (the default) is the one the metric is quoted on, the others "
+                         "run the same one-shot step at their batch shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -144,7 +173,7 @@ def main():
 
     fsr.load_library()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    b = workloads.make_batch(2)
+    b = workloads.make_batch(args.workload)
     step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002)
 
     if args.calibrate_copy:
@@ -208,14 +237,14 @@ def main():
         "metric": "verified_draft_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "cfg2 llama3_8b_layer: B=16, 32 q / 8 kv heads, D=128, bf16 paged KV (page 16, permuted), "
-                               "ctx U[1024,4096], spec U[1,8], vocab 128256",
+        "config": {"workload": WORKLOADS[args.workload],
                    "layers_per_step": args.layers, "rows": b.N, "drafts_per_step": drafts,
                    "kv_tokens": b.kv_tokens(), "launch": "hip_graph" if graph is not None else "eager",
-                   "attention_ms_per_layer": attn_ms, "accept_prune_ms": tail_ms, "seed": b.seed},
+                   "attention_ms_per_layer": attn_ms, "accept_prune_ms": tail_ms, "seed": b.seed,
+                   "distinct_kv_caches": st["n_caches"], "kv_cache_bytes": st["kv_bytes"]},
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel (verify_attention, one launch per layer call)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(), "algorithmic_bytes_per_launch": attn_bytes,
+                     "traffic": measured_traffic(args.workload), "algorithmic_bytes_per_launch": attn_bytes,
                      "launch_us": attn_ms * 1e3},
     }
     if not args.no_cpu_baseline:
