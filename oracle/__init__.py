@@ -154,6 +154,26 @@ def prune_restore(compact, dst_row, *, pad_byte=0):
     return out.view(comp.dtype).reshape((N,) + row_shape), has
 
 
+def topk_rank_check(logits, draft_tokens, cu_q, cu_d, *, K, dtype="f32"):
+    """Sec. 3.2 / Sec. 4 early-exit check: rank of every draft among its row's scores and the
+    (not yet suffix-closed) keep mask over the active rows.  ``logits`` [N, V] is fp32, or bf16 bit
+    patterns (uint16) with dtype="bf16"."""
+    lib = _load()
+    z = _c(logits, np.float32 if dtype == "f32" else np.uint16)
+    toks, cq, cd = _c(draft_tokens, np.int32), _c(cu_q, np.int32), _c(cu_d, np.int32)
+    B = len(cq) - 1
+    N, N_d = int(cq[-1]), int(cd[-1])
+    V = z.shape[1]
+    assert z.shape[0] >= N and len(toks) >= N_d
+    rank = np.full(N_d, -1, np.int32)
+    keep = np.zeros(N, np.uint8)
+    rc = lib.fo_topk_rank_check(_p(z), _p(toks), _p(cq), _p(cd), _p(rank), _p(keep), ctypes.c_int(B), ctypes.c_int(V),
+                                ctypes.c_int(int(K)), ctypes.c_int(F32 if dtype == "f32" else BF16))
+    if rc != 0:
+        raise ValueError(f"fo_topk_rank_check: {rc}")
+    return dict(rank=rank, keep=keep)
+
+
 def verify_chunked(batch, chunks: List[np.ndarray], *, with_attention=True, mode=PROBS, temperature=1.0):
     """Frontier (chunked) verification of one step, Sec. 3.3.
 

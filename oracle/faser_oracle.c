@@ -32,6 +32,10 @@
  *                        rejection every speculative token beyond it is discarded.
  *   fo_prune_restore     Sec. 3.2 / Sec. 4: pruned positions are padded back to the
  *                        original layout; pruned rows carry no values.
+ *   fo_topk_rank_check   Sec. 3.2: a drafted token outside the Top-K set of the
+ *                        intermediate logits becomes a pruning candidate; Sec. 4: the
+ *                        Top-K set is not materialised, it is only checked whether at
+ *                        least K tokens exceed the drafted token's score.
  */
 #include <math.h>
 #include <stdint.h>
@@ -339,6 +343,51 @@ int fo_prune_restore(const uint8_t *compact, const int32_t *dst_row, uint8_t *re
         } else {
             memset(restored + (int64_t)r * row_bytes, pad, (size_t)row_bytes);
             has_value[r] = 0;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Early-exit rank check (Sec. 3.2 token-level decision, Sec. 4 implementation note).
+ *
+ * Request i owns the logit rows cu_q[i] .. cu_q[i+1]-1 (its active query rows, q_i of them)
+ * and the drafts cu_d[i] .. cu_d[i+1]-1 (d_i of them).  Row j holds the model's scores for
+ * the token that follows the row's input, which is draft j of the request, so for
+ * j < min(q_i, d_i)
+ *     rank[cu_d[i] + j] = number of v with z[row j][v] > z[row j][draft j]      (strictly)
+ * and the draft passes iff rank < K (it lies inside the Top-K set).  Drafts with no active
+ * row get rank -1; a draft id outside [0, V) gets rank V (never passes).
+ *
+ * keep [N]: keep[cu_q[i]] = 1 (the row of the last committed token is never pruned);
+ * keep[cu_q[i] + j + 1] = (rank of draft j < K) for j + 1 < q_i: the row whose input is
+ * draft j survives iff draft j passes.  The mask is not suffix-closed here; fo_prune_compact
+ * closes it.
+ */
+int fo_topk_rank_check(const void *logits, const int32_t *draft_tokens, const int32_t *cu_q,
+                       const int32_t *cu_d, int32_t *rank, uint8_t *keep, int B, int V, int K,
+                       int dtype)
+{
+    for (int i = 0; i < B; ++i) {
+        const int q_i = cu_q[i + 1] - cu_q[i], d_i = cu_d[i + 1] - cu_d[i];
+        for (int j = 0; j < d_i; ++j)
+            rank[cu_d[i] + j] = -1;
+        for (int j = 0; j < q_i; ++j)
+            keep[cu_q[i] + j] = 1;
+        for (int j = 0; j < q_i && j < d_i; ++j) {
+            const int64_t row = cu_q[i] + j;
+            const int tok = draft_tokens[cu_d[i] + j];
+            int count = V;
+            if (tok >= 0 && tok < V) {
+                const double mine = load_elem(logits, row * V + tok, dtype);
+                count = 0;
+                for (int v = 0; v < V; ++v)
+                    if (load_elem(logits, row * V + v, dtype) > mine)
+                        ++count;
+            }
+            rank[cu_d[i] + j] = count;
+            if (j + 1 < q_i)
+                keep[cu_q[i] + j + 1] = count < K ? 1 : 0;
         }
     }
     return 0;
