@@ -86,6 +86,17 @@ typedef struct fsr_prune_params {
     int32_t reserved;     /* must be 0 */
 } fsr_prune_params;
 
+/* Static shape of one early-exit rank check. */
+typedef struct fsr_rank_params {
+    int32_t B;        /* requests */
+    int32_t N_cap;    /* rows allocated in logits / keep_mask; cu_q[B] <= N_cap */
+    int32_t D_cap;    /* entries allocated in draft_tokens / rank; cu_d[B] <= D_cap <= 65535 */
+    int32_t V;        /* scores per row (> 0) */
+    int32_t K;        /* a draft passes iff fewer than K scores exceed its own (>= 0) */
+    int32_t dtype;    /* FSR_F32 or FSR_BF16: element type of logits */
+    int32_t reserved; /* must be 0 */
+} fsr_rank_params;
+
 /* Static description of the last failure on the calling thread ("" if none).  Host. */
 const char* fsr_last_error(void);
 
@@ -197,6 +208,32 @@ int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, int32_t* ne
 int fsr_prune_restore(const void* compact, const int32_t* dst_row, void* restored,
                       uint8_t* has_value, size_t row_bytes, int32_t N, uint32_t pad_word,
                       void* stream);
+
+/*
+ * Early-exit rank check (Sec. 3.2: a drafted token that falls outside the Top-K set of the
+ * intermediate logits is marked unlikely to be accepted and becomes a pruning candidate; Sec. 4:
+ * the Top-K set is not materialised, it is only checked whether at least K tokens exceed the
+ * drafted token's score).
+ *
+ * Request i owns the score rows cu_q[i] .. cu_q[i+1]-1 (its active query rows, q_i of them) and the
+ * drafts cu_d[i] .. cu_d[i+1]-1 (d_i of them).  Row j scores the token that follows the row's
+ * input, which is draft j of the request, so for j < min(q_i, d_i)
+ *     rank[cu_d[i] + j] = number of v with logits[row j][v] > logits[row j][draft j]   (strictly)
+ * Drafts without an active row (q_i <= j: pruned earlier) get rank -1, a draft id outside [0, V)
+ * gets rank V.  keep_mask[cu_q[i]] = 1 (the row of the last committed token always stays);
+ * keep_mask[cu_q[i] + j + 1] = (rank of draft j < K) for j + 1 < q_i.  The mask is not
+ * suffix-closed: fsr_prune_compact (suffix_close = 1) drops everything behind the first failing
+ * draft, fsr_prune_restore brings the survivors back to the original layout.
+ *
+ *   logits       [N_cap, V] dtype, row-major, rows contiguous
+ *   draft_tokens [D_cap] int32      rank [D_cap] int32 (out; entries >= cu_d[B] not written)
+ *   keep_mask    [N_cap] uint8 (out; rows >= cu_q[B] not written)
+ * Reads each checked row once (4 V or 2 V bytes) and nothing else of size.  Asynchronous on
+ * `stream`; needs no workspace.
+ */
+int fsr_topk_rank_check(const void* logits, const int32_t* draft_tokens, const int32_t* cu_q,
+                        const int32_t* cu_d, int32_t* rank, uint8_t* keep_mask,
+                        const fsr_rank_params* p /*host*/, void* stream);
 
 /*
  * Keep mask after a one-shot accept step (Sec. 2.1: the rejected suffix is discarded): row j of

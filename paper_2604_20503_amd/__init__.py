@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     prune_scatter,
     spec_accept,
     survivor_mask,
+    topk_rank_check,
     verify_attention,
     version,
 )
@@ -28,5 +29,5 @@ from .frontier import verify_chunked  # noqa: F401
 __all__ = [
     "FsrError", "accept_workspace_bytes", "attn_workspace_bytes", "frontier_commit", "frontier_init",
     "frontier_plan", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
-    "spec_accept", "survivor_mask", "verify_attention", "verify_chunked", "version",
+    "spec_accept", "survivor_mask", "topk_rank_check", "verify_attention", "verify_chunked", "version",
 ]

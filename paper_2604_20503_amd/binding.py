@@ -22,7 +22,7 @@ PROBS, LOGITS = 0, 1
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
-    "fsr_prune_scatter", "fsr_survivor_mask", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
+    "fsr_prune_scatter", "fsr_survivor_mask", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
 
 
@@ -46,6 +46,10 @@ class AcceptParams(ctypes.Structure):
 class PruneParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("N_cap", ctypes.c_int32), ("suffix_close", ctypes.c_int32),
                 ("reserved", ctypes.c_int32)]
+
+
+class RankParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "N_cap", "D_cap", "V", "K", "dtype", "reserved")]
 
 
 def library_path() -> str:
@@ -229,6 +233,26 @@ def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None, payload_o
     if payload is not None:
         res["payload"] = payload_out
     return res
+
+
+def topk_rank_check(logits, draft_tokens, cu_q, cu_d, *, K, rank=None, keep_mask=None):
+    """fsr_topk_rank_check.  logits [N_cap, V] fp32 or bf16; returns (rank [D_cap] int32, keep_mask [N_cap] uint8)."""
+    lib = load_library()
+    N_cap, V = logits.shape
+    D_cap = draft_tokens.shape[0]
+    B = cu_q.shape[0] - 1
+    if cu_d.shape[0] != B + 1:
+        raise ValueError("cu_q and cu_d must both have B+1 entries")
+    if rank is None:
+        rank = torch.empty(D_cap, dtype=torch.int32, device=logits.device)
+    if keep_mask is None:
+        keep_mask = torch.empty(N_cap, dtype=torch.uint8, device=logits.device)
+    p = RankParams(B=B, N_cap=N_cap, D_cap=D_cap, V=V, K=int(K), dtype=_code(logits.dtype), reserved=0)
+    _check(lib.fsr_topk_rank_check(
+        _ptr(logits, name="logits"), _ptr(draft_tokens if D_cap else None, torch.int32, "draft_tokens"),
+        _ptr(cu_q, torch.int32, "cu_q"), _ptr(cu_d, torch.int32, "cu_d"), _ptr(rank if D_cap else None, torch.int32, "rank"),
+        _ptr(keep_mask, torch.uint8, "keep_mask"), ctypes.byref(p), _stream()))
+    return rank, keep_mask
 
 
 def prune_restore(compact, dst_row, *, pad_word=0, restored=None, has_value=None):

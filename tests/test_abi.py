@@ -38,6 +38,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.AttnParams) == 13 * 4
     assert ctypes.sizeof(binding.AcceptParams) == 32 and binding.AcceptParams.temperature.offset == 16
     assert ctypes.sizeof(binding.PruneParams) == 16
+    assert ctypes.sizeof(binding.RankParams) == 7 * 4
 
 
 def test_host_detectable_errors(lib):
@@ -80,6 +81,14 @@ def test_host_detectable_errors(lib):
                                  ctypes.byref(pr), None) == -2   # row_bytes not a multiple of 4
     assert lib.fsr_prune_restore(one, one, one, None, ctypes.c_size_t(6), 4, 0, None) == -2
     assert lib.fsr_frontier_init(None, None, None, None, None, None, 3, 4, None) == -1
+    rk = b.RankParams(B=2, N_cap=8, D_cap=6, V=0, K=10, dtype=0, reserved=0)
+    assert lib.fsr_topk_rank_check(one, one, one, one, one, one, ctypes.byref(rk), None) == -1      # V = 0
+    rk.V = 100; rk.dtype = 5
+    assert lib.fsr_topk_rank_check(one, one, one, one, one, one, ctypes.byref(rk), None) == -3
+    rk.dtype = 0
+    assert lib.fsr_topk_rank_check(None, one, one, one, one, one, ctypes.byref(rk), None) == -1     # logits null
+    rk.D_cap = 70000
+    assert lib.fsr_topk_rank_check(one, one, one, one, one, one, ctypes.byref(rk), None) == -3
     assert lib.fsr_version().startswith(b"faser_verify")
 
 
