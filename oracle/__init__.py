@@ -22,7 +22,7 @@ _LIB = os.path.join(_HERE, "libfaser_oracle.so")
 _lib = None
 
 F32, BF16 = 0, 1
-PROBS, LOGITS = 0, 1
+PROBS, LOGITS, GREEDY = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -85,6 +85,8 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
 
     Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo[B], cdf_hi[B]).
     """
+    if mode == GREEDY:
+        return greedy_accept(p_target, draft_tokens, cu_t, cu_d, S_max=S_max, t_rows=t_rows, d_rows=d_rows)
     lib = _load()
     p_target, p_draft = _c(p_target, np.float32), _c(p_draft, np.float32)
     V = p_target.shape[1]
@@ -104,6 +106,30 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     if rc != 0:
         raise ValueError(f"fo_spec_accept: {rc}")
     return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=lo, cdf_hi=hi)
+
+
+def greedy_accept(target, draft_tokens, cu_t, cu_d, *, S_max, t_rows=None, d_rows=None):
+    """Sec. 2.1 at temperature 0: drafts are accepted while they equal the target row's arg-max (lowest id
+    among equal maxima); the next row's arg-max is the token after the accepted run.
+
+    Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo, cdf_hi) (the last two all NaN:
+    nothing is drawn)."""
+    lib = _load()
+    z = _c(target, np.float32)
+    V = z.shape[1]
+    toks = _c(draft_tokens, np.int32)
+    cu_t, cu_d = _c(cu_t, np.int32), _c(cu_d, np.int32)
+    tr = None if t_rows is None else _c(t_rows, np.int32)
+    dr = None if d_rows is None else _c(d_rows, np.int32)
+    B = len(cu_t) - 1
+    acc = np.zeros(B, np.int32)
+    nem = np.zeros(B, np.int32)
+    em = np.full((B, S_max + 1), -1, np.int32)
+    rc = lib.fo_greedy_accept(_p(z), _p(toks), _p(cu_t), _p(cu_d), _p(tr), _p(dr), _p(acc), _p(nem), _p(em),
+                              ctypes.c_int(B), ctypes.c_int(V), ctypes.c_int(S_max))
+    if rc != 0:
+        raise ValueError(f"fo_greedy_accept: {rc}")
+    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=np.full(B, np.nan), cdf_hi=np.full(B, np.nan))
 
 
 def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None):

@@ -27,6 +27,10 @@
  *                        sampling (accept with probability min(1, p/q); recovery token
  *                        from the normalised positive part of p - q; a bonus token from
  *                        the target when every draft is accepted).
+ *   fo_greedy_accept     the same accept-until-first-mismatch rule at temperature 0: the
+ *                        target's choice at a position is its arg-max token, a draft
+ *                        matches iff it is that token, and the token "resampled from the
+ *                        target" after the accepted run is the arg-max of the next row.
  *   fo_prune_compact     Sec. 3.2: rows predicted/observed to be in the rejected suffix
  *                        are pruned and only the remaining rows proceed; Sec. 3.3: on a
  *                        rejection every speculative token beyond it is discarded.
@@ -273,6 +277,78 @@ int fo_spec_accept(const float *p_target, const float *p_draft, const int32_t *d
         }
         free(p);
         free(qv);
+    }
+    return status;
+}
+
+/*
+ * Greedy verification (Sec. 2.1 at temperature 0: accept the drafted tokens until the first
+ * one that differs from the target's own choice, discard the rest, and take the target's
+ * token at the first mismatch; with every draft accepted the extra target row gives the
+ * bonus token).
+ *
+ * `target` is [rows, V] fp32, probabilities or logits alike: only the position of the row
+ * maximum matters.  The arg-max of a row is the LOWEST token id holding the row's maximum.
+ * Row layout, t_rows / d_rows maps and outputs as in fo_spec_accept; no uniforms, no draft
+ * distributions.
+ *
+ *   n = 0; while n < d_i and draft n == argmax(target row n): n++
+ *   rejected (n < d_i): token = argmax(target row n)
+ *   all accepted and t_i = d_i + 1: token = argmax(target row d_i)
+ *   all accepted and t_i = d_i: no extra token
+ */
+static int argmax_row(const float *rows, int64_t r, int V)
+{
+    int best = 0;
+    for (int v = 1; v < V; ++v)
+        if ((double)rows[r * V + v] > (double)rows[r * V + best])
+            best = v;
+    return best;
+}
+
+int fo_greedy_accept(const float *target, const int32_t *draft_tokens, const int32_t *cu_t,
+                     const int32_t *cu_d, const int32_t *t_rows, const int32_t *d_rows,
+                     int32_t *accepted_len, int32_t *n_emitted, int32_t *emitted, int B, int V,
+                     int S_max)
+{
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < B; ++i) {
+        const int d_i = cu_d[i + 1] - cu_d[i];
+        const int t_i = cu_t[i + 1] - cu_t[i];
+        int32_t *em = emitted + (int64_t)i * (S_max + 1);
+        for (int s = 0; s <= S_max; ++s)
+            em[s] = -1;
+        accepted_len[i] = 0;
+        n_emitted[i] = 0;
+        if (d_i > S_max || t_i < d_i || t_i > d_i + 1) {
+#pragma omp atomic write
+            status = -2;
+            continue;
+        }
+        int n = 0, tok = -1;
+        while (n < d_i) {
+            const int64_t tr = t_rows ? t_rows[cu_t[i] + n] : cu_t[i] + n;
+            const int64_t dr = d_rows ? d_rows[cu_d[i] + n] : cu_d[i] + n;
+            const int choice = argmax_row(target, tr, V);
+            if (draft_tokens[dr] != choice) {
+                tok = choice; /* the target's token at the first mismatch */
+                break;
+            }
+            em[n] = choice;
+            ++n;
+        }
+        accepted_len[i] = n;
+        if (n == d_i && t_i == d_i + 1) {
+            const int64_t tr = t_rows ? t_rows[cu_t[i] + d_i] : cu_t[i] + d_i;
+            tok = argmax_row(target, tr, V);
+        }
+        if (tok >= 0) {
+            em[n] = tok;
+            n_emitted[i] = n + 1;
+        } else {
+            n_emitted[i] = n;
+        }
     }
     return status;
 }

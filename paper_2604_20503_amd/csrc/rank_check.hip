@@ -97,6 +97,8 @@ __global__ __launch_bounds__(kThreads) void rank_count_kernel(RankArgs a) {
     const u32x4* vec = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.logits) + base + body0);
     for (int k = threadIdx.x; k < n_vec; k += kThreads) {
         const u32x4 w = vec[k];
+        // elements go to scalars first: __builtin_bit_cast applied to a vector-element expression was
+        // seen to read element 0 for every index
         const uint32_t w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
         if constexpr (sizeof(T) == 4) {
             count += (__builtin_bit_cast(float, w0) > mine) + (__builtin_bit_cast(float, w1) > mine) +
