@@ -45,7 +45,7 @@ extern "C" {
 #define FSR_EHIP (-5)   /* HIP runtime error at launch */
 
 enum { FSR_F32 = 0, FSR_BF16 = 1 };
-enum { FSR_PROBS = 0, FSR_LOGITS = 1 };
+enum { FSR_PROBS = 0, FSR_LOGITS = 1, FSR_GREEDY = 2 };
 
 /* Static shape of one attention call. */
 typedef struct fsr_attn_params {
@@ -72,7 +72,8 @@ typedef struct fsr_accept_params {
     int32_t B;         /* requests */
     int32_t V;         /* vocabulary size (> 0) */
     int32_t S_max;     /* max drafts per request in this call; emitted has S_max+1 columns */
-    int32_t mode;      /* FSR_PROBS: rows are probabilities; FSR_LOGITS: rows are logits */
+    int32_t mode;      /* FSR_PROBS: rows are probabilities; FSR_LOGITS: rows are logits;
+                          FSR_GREEDY: temperature 0, only the arg-max of a target row matters */
     double temperature; /* LOGITS mode: p = softmax(z / temperature), > 0; ignored in PROBS mode */
     int32_t reserved;  /* must be 0 */
     int32_t reserved2; /* must be 0 */
@@ -172,6 +173,12 @@ int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_
  *   accepted_len [B] int32 (n), n_emitted [B] int32, emitted [B, S_max+1] int32 padded -1
  * Requests with d_i > S_max or t_i - d_i outside {0,1} get accepted_len = n_emitted = -1.
  * Draft token ids are clamped into [0, V).
+ *
+ * FSR_GREEDY mode (the same rule at temperature 0): draft n is accepted iff it equals the
+ * arg-max token of target row n (the lowest id among equal maxima); the token after the
+ * accepted run is the arg-max of the next target row (the row of the first mismatch, or
+ * the bonus row).  p_target may hold probabilities or logits; p_draft, u_accept and
+ * u_sample are not read and may be null.  Every target row of the call is read once.
  */
 int fsr_spec_accept(const float* p_target, const float* p_draft, const int32_t* draft_tokens,
                     const float* u_accept, const float* u_sample, const int32_t* cu_t,

@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libfaser_verify.so")
 _lib = None
 
 F32, BF16 = 0, 1
-PROBS, LOGITS = 0, 1
+PROBS, LOGITS, GREEDY = 0, 1, 2
 
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention",
@@ -168,7 +168,7 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
                 mode=PROBS, temperature=1.0, accepted_len=None, n_emitted=None, emitted=None, workspace=None):
     """fsr_spec_accept.  Returns (accepted_len [B], n_emitted [B], emitted [B, S_max+1])."""
     lib = load_library()
-    B = u_sample.shape[0]
+    B = cu_t.shape[0] - 1
     V = p_target.shape[1]
     dev = p_target.device
     p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), reserved=0, reserved2=0)

@@ -22,6 +22,7 @@
 
 #include "common.hpp"
 #include "device_utils.hpp"
+#include "greedy_accept.hpp"
 
 namespace fsr {
 namespace {
@@ -443,7 +444,7 @@ int validate(const fsr_accept_params* p, const char* who) {
     if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
     if (p->B < 0 || p->V <= 0 || p->S_max < 0 || p->reserved != 0 || p->reserved2 != 0)
         return fail(FSR_EINVAL, "%s: B=%d V=%d S_max=%d reserved=%d", who, p->B, p->V, p->S_max, p->reserved);
-    if (p->mode != FSR_PROBS && p->mode != FSR_LOGITS) return fail(FSR_EUNSUP, "%s: mode=%d", who, p->mode);
+    if (p->mode != FSR_PROBS && p->mode != FSR_LOGITS && p->mode != FSR_GREEDY) return fail(FSR_EUNSUP, "%s: mode=%d", who, p->mode);
     if (p->mode == FSR_LOGITS && !(p->temperature > 0.0)) return fail(FSR_EINVAL, "%s: temperature=%g must be > 0", who, p->temperature);
     if ((long long)p->B * (2LL * p->S_max + 1) > 65535) return fail(FSR_EUNSUP, "%s: B*(2*S_max+1)=%lld exceeds 65535 rows per call", who, (long long)p->B * (2LL * p->S_max + 1));
     return FSR_OK;
@@ -458,7 +459,7 @@ extern "C" int fsr_accept_workspace_bytes(const fsr_accept_params* p, size_t* ou
     int rc = validate(p, "fsr_accept_workspace_bytes");
     if (rc != FSR_OK) return rc;
     if (!out_bytes) return fail(FSR_EINVAL, "fsr_accept_workspace_bytes: out_bytes is null");
-    *out_bytes = carve(*p, nullptr, nullptr);
+    *out_bytes = p->mode == FSR_GREEDY ? greedy_workspace_bytes(*p) : carve(*p, nullptr, nullptr);
     return FSR_OK;
 }
 
@@ -470,6 +471,16 @@ extern "C" int fsr_spec_accept(const float* p_target, const float* p_draft, cons
     int rc = validate(p, "fsr_spec_accept");
     if (rc != FSR_OK) return rc;
     if (p->B == 0) return FSR_OK;
+    if (p->mode == FSR_GREEDY) {
+        if (!p_target || !cu_t || !cu_d || !accepted_len || !n_emitted || !emitted)
+            return fail(FSR_EINVAL, "fsr_spec_accept: null pointer among p_target/cu_t/cu_d/outputs");
+        if (p->S_max > 0 && !draft_tokens) return fail(FSR_EINVAL, "fsr_spec_accept: draft_tokens is null with S_max=%d", p->S_max);
+        const size_t need_g = greedy_workspace_bytes(*p);
+        if (!workspace || ws_bytes < need_g) return fail(FSR_EWS, "fsr_spec_accept: workspace %zu bytes, need %zu", ws_bytes, need_g);
+        if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "fsr_spec_accept: workspace must be 256-byte aligned");
+        return greedy_accept_launch(p_target, draft_tokens, cu_t, cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, *p,
+                                    workspace, (hipStream_t)stream);
+    }
     if (!p_target || !u_sample || !cu_t || !cu_d || !accepted_len || !n_emitted || !emitted)
         return fail(FSR_EINVAL, "fsr_spec_accept: null pointer among p_target/u_sample/cu_t/cu_d/outputs");
     if (p->S_max > 0 && (!p_draft || !draft_tokens || !u_accept))

@@ -79,13 +79,14 @@ def check_accept(gpu, ref, u_sample):
     return int(frag.sum()), len(diff_rows)
 
 
-def chunked_case(fsr, oracle, b, chunks, dtype):
+def chunked_case(fsr, oracle, b, chunks, dtype, mode="probs"):
     """Frontier verification of batch ``b`` through the C ABI against the chunked oracle and the
     one-shot accept: lengths bit-exact, tokens bit-exact except fragile draws, exactly the same rows
     computed, attention rows within tolerance, same number of rows processed."""
-    ref = oracle.verify_chunked(b, chunks)
+    o_mode, g_mode = (oracle.GREEDY, 2) if mode == "greedy" else (oracle.PROBS, 0)
+    ref = oracle.verify_chunked(b, chunks, mode=o_mode)
     one = oracle.spec_accept(b.p_target, b.p_draft, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d,
-                             S_max=b.S_max)
+                             S_max=b.S_max, mode=o_mode)
     assert np.array_equal(ref["emitted"], one["emitted"])
     d = DeviceBatch(b)
     out = torch.full(d.q.shape, float("nan"), dtype=torch.float32, device="cuda")
@@ -93,7 +94,7 @@ def chunked_case(fsr, oracle, b, chunks, dtype):
                            ctx_lens=d.ctx_lens, spec_lens=d.spec_lens, cu_q=d.cu_q, cu_d=d.cu_d, p_target=d.p_target,
                            p_draft=d.p_draft, draft_tokens=d.draft_tokens, u_accept=d.u_accept, u_sample=d.u_sample,
                            chunks=[dev(c) for c in chunks], scale=b.scale, S_total_max=b.S_max,
-                           chunk_S_max=int(max(c.max() for c in chunks)), out=out)
+                           chunk_S_max=int(max(c.max() for c in chunks)), out=out, mode=g_mode)
     torch.cuda.synchronize()
     assert np.array_equal(r["accepted_len"].cpu().numpy(), ref["accepted_len"])
     assert np.array_equal(r["n_emitted"].cpu().numpy(), ref["n_emitted"])
