@@ -180,6 +180,22 @@ def prune_restore(compact, dst_row, *, pad_byte=0):
     return out.view(comp.dtype).reshape((N,) + row_shape), has
 
 
+def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, P):
+    """Store this call's key / value rows ([N, H_kv, D]) into copies of the paged caches
+    ([n_pages, H_kv, P, D]) at positions ctx_lens[i] + j; returns the two new caches."""
+    lib = _load()
+    kc, vc = np.array(k_cache, copy=True, order="C"), np.array(v_cache, copy=True, order="C")
+    kn, vn = np.ascontiguousarray(k_new), np.ascontiguousarray(v_new)
+    assert kn.dtype == kc.dtype and vn.dtype == vc.dtype and kn.shape == vn.shape
+    bt, ctx, cu = _c(block_tables, np.int32), _c(ctx_lens, np.int32), _c(cu_q, np.int32)
+    B = len(ctx)
+    H_kv, D = kc.shape[1], kc.shape[3]
+    assert kc.shape[2] == P and kn.shape[1:] == (H_kv, D)
+    lib.fo_kv_append(_p(kn), _p(vn), _p(kc), _p(vc), _p(bt), _p(ctx), _p(cu), ctypes.c_int(B), ctypes.c_int(H_kv),
+                     ctypes.c_int(D), ctypes.c_int(P), ctypes.c_int(bt.shape[1]), ctypes.c_int(kc.dtype.itemsize))
+    return kc, vc
+
+
 def topk_rank_check(logits, draft_tokens, cu_q, cu_d, *, K, dtype="f32"):
     """Sec. 3.2 / Sec. 4 early-exit check: rank of every draft among its row's scores and the
     (not yet suffix-closed) keep mask over the active rows.  ``logits`` [N, V] is fp32, or bf16 bit

@@ -27,6 +27,10 @@
  *                        sampling (accept with probability min(1, p/q); recovery token
  *                        from the normalised positive part of p - q; a bonus token from
  *                        the target when every draft is accepted).
+ *   fo_kv_append         Sec. 2.1 / Sec. 3.1: the drafted tokens of a request enter the
+ *                        target model as new positions behind its cached context; their
+ *                        keys and values are stored into the request's pages before the
+ *                        attention of the same forward pass reads them.
  *   fo_greedy_accept     the same accept-until-first-mismatch rule at temperature 0: the
  *                        target's choice at a position is its arg-max token, a draft
  *                        matches iff it is that token, and the token "resampled from the
@@ -464,6 +468,37 @@ int fo_topk_rank_check(const void *logits, const int32_t *draft_tokens, const in
             rank[cu_d[i] + j] = count;
             if (j + 1 < q_i)
                 keep[cu_q[i] + j + 1] = count < K ? 1 : 0;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Store the keys / values of this call's rows into the paged caches.
+ *
+ * Row j of request i (row cu_q[i] + j of k_new / v_new, each [N, H_kv, D]) is the token at
+ * logical position t = ctx_lens[i] + j; it goes to page block_tables[i * max_pages + t / P],
+ * slot t % P, of caches laid out [n_pages, H_kv, P, D].  Positions at or beyond max_pages * P
+ * are not stored.  elem_bytes is the size of one element (2 for bf16, 4 for fp32); values
+ * are copied bit for bit.
+ */
+int fo_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                 const int32_t *block_tables, const int32_t *ctx_lens, const int32_t *cu_q, int B,
+                 int H_kv, int D, int P, int max_pages, int elem_bytes)
+{
+    const int64_t vec = (int64_t)D * elem_bytes;
+    for (int i = 0; i < B; ++i) {
+        for (int r = cu_q[i]; r < cu_q[i + 1]; ++r) {
+            const int64_t t = (int64_t)ctx_lens[i] + (r - cu_q[i]);
+            if (t < 0 || t >= (int64_t)max_pages * P)
+                continue;
+            const int64_t page = block_tables[(int64_t)i * max_pages + t / P];
+            for (int g = 0; g < H_kv; ++g) {
+                const int64_t src = ((int64_t)r * H_kv + g) * vec;
+                const int64_t dst = ((page * H_kv + g) * P + t % P) * vec;
+                memcpy((uint8_t *)k_cache + dst, (const uint8_t *)k_new + src, (size_t)vec);
+                memcpy((uint8_t *)v_cache + dst, (const uint8_t *)v_new + src, (size_t)vec);
+            }
         }
     }
     return 0;
