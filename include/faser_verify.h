@@ -141,6 +141,22 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
                          const fsr_attn_params* p /*host*/, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/*
+ * Cache append (Sec. 2.1 / Sec. 3.1: the drafted tokens of a request enter the target model as
+ * new positions behind its cached context).  Row j of request i (row cu_q[i] + j of k_new /
+ * v_new) is the token at logical position ctx_lens[i] + j: its key and value vectors are copied,
+ * bit for bit, to page block_tables[i * max_pages + t / P], slot t % P of the caches.  Call it
+ * before fsr_verify_attention of the same rows (same stream).
+ *
+ *   k_new, v_new  [N_cap, H_kv, D] dtype; rows >= cu_q[B] are not read
+ *   k_cache, v_cache, block_tables, ctx_lens, cu_q and *p as for fsr_verify_attention (H_q, scale,
+ *   out_dtype, max_q_len and flags are ignored; D * element size must be a multiple of 16)
+ * Positions at or beyond max_pages * P and page ids outside [0, n_pages) are skipped.
+ */
+int fsr_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                  const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q,
+                  const fsr_attn_params* p /*host*/, void* stream);
+
 /* Workspace bytes needed by fsr_spec_accept for shapes up to *p (host query). */
 int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_bytes /*host*/);
 

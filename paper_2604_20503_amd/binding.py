@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 PROBS, LOGITS, GREEDY = 0, 1, 2
 
 SYMBOLS = [
-    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention",
+    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_kv_append",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
@@ -155,6 +155,24 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
         _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _ptr(workspace, name="workspace"),
         ctypes.c_size_t(ws_bytes), _stream()))
     return out, lse
+
+
+def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q):
+    """fsr_kv_append: store the call's key / value rows [N_cap, H_kv, D] into the paged caches (in place)."""
+    lib = load_library()
+    B = ctx_lens.shape[0]
+    n_pages, H_kv, P, D = k_cache.shape
+    if k_new.shape != v_new.shape or k_new.shape[1:] != (H_kv, D) or v_cache.shape != k_cache.shape:
+        raise ValueError("k_new/v_new must be [N_cap, H_kv, D] matching the caches")
+    if not (k_new.dtype == v_new.dtype == k_cache.dtype == v_cache.dtype):
+        raise ValueError("k_new, v_new and the caches must share a dtype")
+    p = AttnParams(B=B, N_cap=k_new.shape[0], H_q=H_kv, H_kv=H_kv, D=D, P=P, max_pages=block_tables.shape[1],
+                   n_pages=n_pages, dtype=_code(k_new.dtype), out_dtype=_code(k_new.dtype), scale=1.0, max_q_len=0,
+                   reserved=0)
+    _check(lib.fsr_kv_append(_ptr(k_new, name="k_new"), _ptr(v_new, name="v_new"), _ptr(k_cache, name="k_cache"),
+                             _ptr(v_cache, name="v_cache"), _ptr(block_tables, torch.int32, "block_tables"),
+                             _ptr(ctx_lens, torch.int32, "ctx_lens"), _ptr(cu_q, torch.int32, "cu_q"), ctypes.byref(p),
+                             _stream()))
 
 
 def accept_workspace_bytes(*, B, V, S_max, mode=PROBS, temperature=1.0) -> int:

@@ -81,6 +81,7 @@ def test_host_detectable_errors(lib):
                                  ctypes.byref(pr), None) == -2   # row_bytes not a multiple of 4
     assert lib.fsr_prune_restore(one, one, one, None, ctypes.c_size_t(6), 4, 0, None) == -2
     assert lib.fsr_frontier_init(None, None, None, None, None, None, 3, 4, None) == -1
+    assert lib.fsr_kv_append(None, one, one, one, one, one, one, ctypes.byref(ok), None) == -1   # k_new null
     rk = b.RankParams(B=2, N_cap=8, D_cap=6, V=0, K=10, dtype=0, reserved=0)
     assert lib.fsr_topk_rank_check(one, one, one, one, one, one, ctypes.byref(rk), None) == -1      # V = 0
     rk.V = 100; rk.dtype = 5
