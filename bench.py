@@ -135,6 +135,93 @@ def cpu_baseline(b, n_layers):
                        f"compaction ({t_pr * 1e3:.2f} ms) at full size"), r
 
 
+def overlap_measure(fsr, torch, workloads, b, n_layers, n_draft_cus, reps=5):
+    """Sec. 3.3's spatial sharing on MI355X: the step's attention layers on a stream that owns all but
+    ``n_draft_cus`` compute units, a stand-in drafter on a stream that owns the rest, each timed alone
+    and both at once (eager launches, HIP events on each stream).  The stand-in drafter is the decode
+    attention of a draft-model-shaped batch (8 query / 2 KV heads, D = 128, one row per request, the
+    same context lengths, 8 layers with their own caches, 4 autoregressive steps): HBM-bound like the
+    real one, without its GEMMs."""
+    from paper_2604_20503_amd.streams import split_device
+
+    def dev(x, bf16=False):
+        t = torch.from_numpy(np.ascontiguousarray(x.view(np.int16) if bf16 else x)).cuda()
+        return t.view(torch.bfloat16) if bf16 else t
+
+    draft_s, verify_s = split_device(n_draft_cus)
+    # verification side: the workload's own tensors, 8 distinct caches are enough to stay out of the last-level cache
+    q, bt, ctx, spec, cu_q = dev(b.q, True), dev(b.block_tables), dev(b.ctx_lens), dev(b.spec_lens), dev(b.cu_q)
+    k0, v0 = dev(b.k_cache, True), dev(b.v_cache, True)
+    kv = [(k0, v0)] + [(torch.randn_like(k0, dtype=torch.float32).to(torch.bfloat16),
+                        torch.randn_like(v0, dtype=torch.float32).to(torch.bfloat16)) for _ in range(7)]
+    out = torch.empty_like(q)
+    S = b.S_max + 1
+
+    def ws_for(batch, mq):
+        return torch.empty(max(256, fsr.attn_workspace_bytes(
+            B=batch.B, N_cap=batch.N, H_q=batch.H_q, H_kv=batch.H_kv, D=batch.D, P=batch.P, max_pages=batch.max_pages,
+            n_pages=batch.n_pages, dtype=torch.bfloat16, out_dtype=torch.bfloat16, max_q_len=mq)), dtype=torch.uint8, device="cuda")
+
+    ws_v = ws_for(b, S)
+
+    def verify(n_wg):
+        for l in range(n_layers):
+            k, v = kv[l % len(kv)]
+            fsr.verify_attention(q, k, v, bt, ctx, spec, cu_q, scale=b.scale, out=out, workspace=ws_v, max_q_len=S,
+                                 max_workgroups=n_wg)
+
+    # drafter stand-in
+    db = workloads.make_batch(2, rep=1, with_probs=False, H_q=8, H_kv=2, ctx_lens=b.ctx_lens, spec_lens=[0] * b.B)
+    dq, dbt, dctx, dcu = dev(db.q, True), dev(db.block_tables), dev(db.ctx_lens), dev(db.cu_q)
+    dk0, dv0 = dev(db.k_cache, True), dev(db.v_cache, True)
+    dkv = [(dk0, dv0)] + [(torch.randn_like(dk0, dtype=torch.float32).to(torch.bfloat16),
+                           torch.randn_like(dv0, dtype=torch.float32).to(torch.bfloat16)) for _ in range(7)]
+    dout = torch.empty_like(dq)
+    ws_d = ws_for(db, 1)
+
+    def draft(n_wg):
+        for _ in range(4):
+            for k, v in dkv:
+                fsr.verify_attention(dq, k, v, dbt, dctx, None, dcu, scale=db.scale, out=dout, workspace=ws_d, max_q_len=1,
+                                     max_workgroups=n_wg)
+
+    def timed(jobs):
+        """jobs: list of (stream, fn).  Returns per-job mean ms with all jobs running at once."""
+        for st, fn in jobs:  # warm-up
+            with torch.cuda.stream(st):
+                fn()
+        torch.cuda.synchronize()
+        acc = [0.0] * len(jobs)
+        for _ in range(reps):
+            ev = []
+            for st, fn in jobs:
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                with torch.cuda.stream(st):
+                    a.record(st)
+                    fn()
+                    e.record(st)
+                ev.append((a, e))
+            torch.cuda.synchronize()
+            for i, (a, e) in enumerate(ev):
+                acc[i] += a.elapsed_time(e) / reps
+        return acc
+
+    cur = torch.cuda.current_stream()
+    n_all = draft_s.n_cus + verify_s.n_cus
+    res = {"draft_cus": draft_s.n_cus, "verify_cus": verify_s.n_cus,
+           "verify_ms_whole_device": timed([(cur, lambda: verify(0))])[0],
+           "verify_ms_share_alone": timed([(verify_s.stream, lambda: verify(verify_s.n_cus))])[0],
+           "draft_ms_whole_device": timed([(cur, lambda: draft(0))])[0],
+           "draft_ms_share_alone": timed([(draft_s.stream, lambda: draft(draft_s.n_cus))])[0]}
+    both = timed([(verify_s.stream, lambda: verify(verify_s.n_cus)), (draft_s.stream, lambda: draft(draft_s.n_cus))])
+    res["verify_ms_share_concurrent"], res["draft_ms_share_concurrent"] = both
+    res["serial_ms_whole_device"] = res["verify_ms_whole_device"] + res["draft_ms_whole_device"]
+    res["concurrent_ms"] = max(both)
+    res["note"] = (f"{n_all} compute units split by stream CU masks; stand-in drafter = decode attention of a "
+                   "draft-shaped batch (8 q / 2 kv heads, 8 layers x 4 steps); eager launches")
+    return res
+
+
 def measured_traffic(workload):
     """HBM bytes per attention launch from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE, scaled by a plain copy of known size), or None if there is no summary."""
@@ -159,6 +246,9 @@ def main():
                          "run the same one-shot step at their batch shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", type=int, default=0, metavar="N",
+                    help="also measure the step's attention on a stream that owns all but N compute units next to a "
+                         "stand-in drafter on a stream that owns those N (adds an \"overlap\" object to the JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that hardware byte counters of a "
                          "profiled run can be scaled")
@@ -247,6 +337,8 @@ def main():
                      "traffic": measured_traffic(args.workload), "algorithmic_bytes_per_launch": attn_bytes,
                      "launch_us": attn_ms * 1e3},
     }
+    if args.overlap > 0:
+        result["overlap"] = overlap_measure(fsr, torch, workloads, b, args.layers, args.overlap)
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(b, args.layers)
         result["cpu_baseline"] = base

@@ -64,7 +64,10 @@ typedef struct fsr_attn_params {
                           length + 1), or 0 if unknown.  A performance hint only: it picks the
                           register budget of the kernel; requests with more rows are still
                           computed correctly, in several passes over their keys. */
-    int32_t reserved;  /* must be 0 */
+    int32_t max_workgroups; /* 0: one workgroup per compute unit of the device.  > 0: at most this
+                          many -- for a call enqueued on a stream that owns only part of the
+                          device (Sec. 3.3: drafting and verification share the GPU spatially), so
+                          that the persistent grid matches the compute units it will get. */
 } fsr_attn_params;
 
 /* Static shape of one accept call. */

@@ -1027,9 +1027,9 @@ struct Plan {
 int validate(const fsr_attn_params* p, const char* who) {
     if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
     if (p->max_q_len < 0) return fail(FSR_EINVAL, "%s: max_q_len=%d", who, p->max_q_len);
-    if (p->B < 0 || p->N_cap < 0 || p->H_q <= 0 || p->H_kv <= 0 || p->max_pages <= 0 || p->n_pages <= 0 || p->P <= 0 || p->reserved != 0)
-        return fail(FSR_EINVAL, "%s: B=%d N_cap=%d H_q=%d H_kv=%d max_pages=%d n_pages=%d P=%d reserved=%d", who, p->B, p->N_cap,
-                    p->H_q, p->H_kv, p->max_pages, p->n_pages, p->P, p->reserved);
+    if (p->B < 0 || p->N_cap < 0 || p->H_q <= 0 || p->H_kv <= 0 || p->max_pages <= 0 || p->n_pages <= 0 || p->P <= 0 || p->max_workgroups < 0)
+        return fail(FSR_EINVAL, "%s: B=%d N_cap=%d H_q=%d H_kv=%d max_pages=%d n_pages=%d P=%d max_workgroups=%d", who, p->B, p->N_cap,
+                    p->H_q, p->H_kv, p->max_pages, p->n_pages, p->P, p->max_workgroups);
     if (p->H_q % p->H_kv != 0) return fail(FSR_ESHAPE, "%s: H_q=%d is not a multiple of H_kv=%d", who, p->H_q, p->H_kv);
     if (p->D != 64 && p->D != 128) return fail(FSR_EUNSUP, "%s: head dim %d (64 and 128 are built)", who, p->D);
     if (p->dtype != FSR_F32 && p->dtype != FSR_BF16) return fail(FSR_EUNSUP, "%s: dtype=%d", who, p->dtype);
@@ -1081,6 +1081,7 @@ Plan make_plan(const fsr_attn_params& p) {
     pl.mt_max = mt <= kMaxMT ? (int)mt : 3;
     // the workspace is sized for up to 1024 workgroups so that its size does not depend on the device
     pl.nb = std::min(persistent_blocks(), 1024);
+    if (p.max_workgroups > 0) pl.nb = std::min(pl.nb, p.max_workgroups);
     pl.bytes_o = align_up((size_t)1024 * 2 * 16 * pl.mt_max * kD * sizeof(float), 256);
     pl.bytes_ml = align_up((size_t)1024 * 2 * 16 * pl.mt_max * 2 * sizeof(float), 256);
     pl.bytes_cnt = align_up((size_t)(1024 + 1) * sizeof(unsigned long long), 256);
