@@ -78,7 +78,8 @@ typedef struct fsr_accept_params {
     int32_t mode;      /* FSR_PROBS: rows are probabilities; FSR_LOGITS: rows are logits;
                           FSR_GREEDY: temperature 0, only the arg-max of a target row matters */
     double temperature; /* LOGITS mode: p = softmax(z / temperature), > 0; ignored in PROBS mode */
-    int32_t reserved;  /* must be 0 */
+    int32_t dtype;     /* FSR_F32 (0) or FSR_BF16: element type of the p_target / p_draft rows
+                          (bf16 not in FSR_GREEDY mode) */
     int32_t reserved2; /* must be 0 */
 } fsr_accept_params;
 
@@ -179,8 +180,9 @@ int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_
  * running mass (fp64) is strictly greater than u_sample[i] * total mass; zero-mass tokens
  * are never drawn.  The library draws no random numbers itself.
  *
- *   p_target     [*, V] float32 (probabilities, or logits in FSR_LOGITS mode)
- *   p_draft      [*, V] float32
+ *   p_target     [*, V] dtype (probabilities, or logits in FSR_LOGITS mode); a bf16 value
+ *                counts as the fp32 value with the same leading bits
+ *   p_draft      [*, V] dtype
  *   draft_tokens [*] int32, u_accept [*] float32 in [0,1): indexed like p_draft rows
  *   u_sample     [B] float32 in [0,1)
  *   cu_t, cu_d   [B+1] int32 offsets of the call's target / draft rows
@@ -199,7 +201,7 @@ int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_
  * the bonus row).  p_target may hold probabilities or logits; p_draft, u_accept and
  * u_sample are not read and may be null.  Every target row of the call is read once.
  */
-int fsr_spec_accept(const float* p_target, const float* p_draft, const int32_t* draft_tokens,
+int fsr_spec_accept(const void* p_target, const void* p_draft, const int32_t* draft_tokens,
                     const float* u_accept, const float* u_sample, const int32_t* cu_t,
                     const int32_t* cu_d, const int32_t* t_rows, const int32_t* d_rows,
                     int32_t* accepted_len, int32_t* n_emitted, int32_t* emitted,

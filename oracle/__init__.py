@@ -80,7 +80,7 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, H_q, 
 
 
 def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, *, S_max,
-                t_rows=None, d_rows=None, mode=PROBS, temperature=1.0):
+                t_rows=None, d_rows=None, mode=PROBS, temperature=1.0, dtype="f32"):
     """Sec. 2.1 accept-until-first-mismatch with recovery/bonus token.
 
     Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo[B], cdf_hi[B]).
@@ -88,7 +88,8 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     if mode == GREEDY:
         return greedy_accept(p_target, draft_tokens, cu_t, cu_d, S_max=S_max, t_rows=t_rows, d_rows=d_rows)
     lib = _load()
-    p_target, p_draft = _c(p_target, np.float32), _c(p_draft, np.float32)
+    row_t = np.float32 if dtype == "f32" else np.uint16  # bf16 rows come as bit patterns
+    p_target, p_draft = _c(p_target, row_t), _c(p_draft, row_t)
     V = p_target.shape[1]
     toks, ua, us = _c(draft_tokens, np.int32), _c(u_accept, np.float32), _c(u_sample, np.float32)
     cu_t, cu_d = _c(cu_t, np.int32), _c(cu_d, np.int32)
@@ -102,7 +103,8 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     hi = np.full(B, np.nan)
     rc = lib.fo_spec_accept(_p(p_target), _p(p_draft), _p(toks), _p(ua), _p(us), _p(cu_t), _p(cu_d), _p(tr), _p(dr),
                             _p(acc), _p(nem), _p(em), _p(lo), _p(hi), ctypes.c_int(B), ctypes.c_int(V),
-                            ctypes.c_int(S_max), ctypes.c_int(mode), ctypes.c_double(temperature))
+                            ctypes.c_int(S_max), ctypes.c_int(mode), ctypes.c_double(temperature),
+                            ctypes.c_int(F32 if dtype == "f32" else BF16))
     if rc != 0:
         raise ValueError(f"fo_spec_accept: {rc}")
     return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=lo, cdf_hi=hi)

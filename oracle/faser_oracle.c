@@ -130,23 +130,23 @@ int fo_verify_attention(const void *q, const void *k_cache, const void *v_cache,
 }
 
 /* Probability vector of one row in fp64: the row itself (PROBS) or softmax(z / T) (LOGITS). */
-static void row_probs(const float *rows, int64_t r, int V, int mode, double temperature, double *p)
+static void row_probs(const void *rows, int dtype, int64_t r, int V, int mode, double temperature, double *p)
 {
-    const float *x = rows + r * (int64_t)V;
+    const int64_t base = r * (int64_t)V;
     if (mode == FO_PROBS) {
         for (int v = 0; v < V; ++v)
-            p[v] = (double)x[v];
+            p[v] = load_elem(rows, base + v, dtype);
         return;
     }
     double m = -INFINITY;
     for (int v = 0; v < V; ++v) {
-        const double z = (double)x[v] / temperature;
+        const double z = load_elem(rows, base + v, dtype) / temperature;
         if (z > m)
             m = z;
     }
     double Z = 0.0;
     for (int v = 0; v < V; ++v) {
-        p[v] = exp((double)x[v] / temperature - m);
+        p[v] = exp(load_elem(rows, base + v, dtype) / temperature - m);
         Z += p[v];
     }
     for (int v = 0; v < V; ++v)
@@ -205,13 +205,14 @@ static int inverse_cdf(const double *r, int V, double u, double *cdf_lo, double 
  * Tokens are drawn by inverse CDF with the single u_sample[i].
  *
  * emitted is [B, S_max+1] padded with -1.  cdf_lo/cdf_hi (nullable, [B]) give the drawn
- * token's CDF interval (NaN if no token was drawn).
+ * token's CDF interval (NaN if no token was drawn).  The rows are fp32, or bf16 bit patterns
+ * (dtype), a bf16 value being the fp32 value with the same leading bits.
  */
-int fo_spec_accept(const float *p_target, const float *p_draft, const int32_t *draft_tokens,
+int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *draft_tokens,
                    const float *u_accept, const float *u_sample, const int32_t *cu_t,
                    const int32_t *cu_d, const int32_t *t_rows, const int32_t *d_rows,
                    int32_t *accepted_len, int32_t *n_emitted, int32_t *emitted, double *cdf_lo,
-                   double *cdf_hi, int B, int V, int S_max, int mode, double temperature)
+                   double *cdf_hi, int B, int V, int S_max, int mode, double temperature, int dtype)
 {
     int status = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -239,11 +240,11 @@ int fo_spec_accept(const float *p_target, const float *p_draft, const int32_t *d
             const int x = draft_tokens[dr];
             double px, qx;
             if (mode == FO_PROBS) {
-                px = (double)p_target[tr * V + x];
-                qx = (double)p_draft[dr * V + x];
+                px = load_elem(p_target, tr * V + x, dtype);
+                qx = load_elem(p_draft, dr * V + x, dtype);
             } else {
-                row_probs(p_target, tr, V, mode, temperature, p);
-                row_probs(p_draft, dr, V, mode, temperature, qv);
+                row_probs(p_target, dtype, tr, V, mode, temperature, p);
+                row_probs(p_draft, dtype, dr, V, mode, temperature, qv);
                 px = p[x];
                 qx = qv[x];
             }
@@ -259,8 +260,8 @@ int fo_spec_accept(const float *p_target, const float *p_draft, const int32_t *d
         if (n < d_i) { /* rejection at position n: recovery token from the residual */
             const int64_t tr = t_rows ? t_rows[cu_t[i] + n] : cu_t[i] + n;
             const int64_t dr = d_rows ? d_rows[cu_d[i] + n] : cu_d[i] + n;
-            row_probs(p_target, tr, V, mode, temperature, p);
-            row_probs(p_draft, dr, V, mode, temperature, qv);
+            row_probs(p_target, dtype, tr, V, mode, temperature, p);
+            row_probs(p_draft, dtype, dr, V, mode, temperature, qv);
             for (int v = 0; v < V; ++v) {
                 const double r = p[v] - qv[v];
                 qv[v] = r > 0.0 ? r : 0.0;
@@ -270,7 +271,7 @@ int fo_spec_accept(const float *p_target, const float *p_draft, const int32_t *d
                 tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0);
         } else if (t_i == d_i + 1) { /* everything accepted: bonus token from the extra target row */
             const int64_t tr = t_rows ? t_rows[cu_t[i] + d_i] : cu_t[i] + d_i;
-            row_probs(p_target, tr, V, mode, temperature, p);
+            row_probs(p_target, dtype, tr, V, mode, temperature, p);
             tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0);
         }
         if (tok >= 0) {

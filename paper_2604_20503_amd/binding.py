@@ -40,7 +40,7 @@ class AttnParams(ctypes.Structure):
 
 class AcceptParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("V", ctypes.c_int32), ("S_max", ctypes.c_int32), ("mode", ctypes.c_int32),
-                ("temperature", ctypes.c_double), ("reserved", ctypes.c_int32), ("reserved2", ctypes.c_int32)]
+                ("temperature", ctypes.c_double), ("dtype", ctypes.c_int32), ("reserved2", ctypes.c_int32)]
 
 
 class PruneParams(ctypes.Structure):
@@ -177,7 +177,7 @@ def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q):
 
 
 def accept_workspace_bytes(*, B, V, S_max, mode=PROBS, temperature=1.0) -> int:
-    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), reserved=0, reserved2=0)
+    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), dtype=F32, reserved2=0)
     out = ctypes.c_size_t(0)
     _check(load_library().fsr_accept_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
     return int(out.value)
@@ -190,7 +190,10 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     B = cu_t.shape[0] - 1
     V = p_target.shape[1]
     dev = p_target.device
-    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), reserved=0, reserved2=0)
+    if p_draft is not None and p_draft.dtype != p_target.dtype:
+        raise ValueError("p_target and p_draft must share a dtype")
+    p = AcceptParams(B=B, V=V, S_max=S_max, mode=mode, temperature=float(temperature), dtype=_code(p_target.dtype),
+                     reserved2=0)
     if accepted_len is None:
         accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
     if n_emitted is None:
@@ -207,7 +210,7 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
         workspace = torch.empty(max(need.value, 256), dtype=torch.uint8, device=dev)
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.fsr_spec_accept(
-        _ptr(p_target, torch.float32, "p_target"), _ptr(p_draft, torch.float32, "p_draft"),
+        _ptr(p_target, name="p_target"), _ptr(p_draft, name="p_draft"),
         _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(u_accept, torch.float32, "u_accept"),
         _ptr(u_sample, torch.float32, "u_sample"), _ptr(cu_t, torch.int32, "cu_t"), _ptr(cu_d, torch.int32, "cu_d"),
         _ptr(t_rows, torch.int32, "t_rows"), _ptr(d_rows, torch.int32, "d_rows"),

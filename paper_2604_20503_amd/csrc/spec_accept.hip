@@ -87,8 +87,15 @@ __device__ __forceinline__ double block_sum(double v, double* smem) {
     return t;
 }
 
+// Rows are fp32, or bf16 stored as 16-bit patterns (the upper half of an fp32).
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); }
+// May four consecutive values starting at a multiple of four be fetched with one vector load?
+__device__ __forceinline__ bool row_vec_ok(const float* row) { return ((uintptr_t)row & 15) == 0; }
+__device__ __forceinline__ bool row_vec_ok(const uint16_t* row) { return ((uintptr_t)row & 7) == 0; }
+
 // Four consecutive values of a row starting at token e (bounds-checked; vector load when
-// the row is 16-byte aligned).
+// the row is aligned for it).
 __device__ __forceinline__ void load_quad(const float* __restrict__ row, int e, int V, bool vec, float (&x)[4]) {
     if (vec && e + 3 < V) {
         const float4 t = *reinterpret_cast<const float4*>(row + e);
@@ -96,6 +103,18 @@ __device__ __forceinline__ void load_quad(const float* __restrict__ row, int e, 
     } else {
 #pragma unroll
         for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? row[e + k] : 0.0f;
+    }
+}
+__device__ __forceinline__ void load_quad(const uint16_t* __restrict__ row, int e, int V, bool vec, float (&x)[4]) {
+    if (vec && e + 3 < V) {
+        const uint2 t = *reinterpret_cast<const uint2*>(row + e);
+        x[0] = __builtin_bit_cast(float, t.x << 16);
+        x[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
+        x[2] = __builtin_bit_cast(float, t.y << 16);
+        x[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? to_float(row[e + k]) : 0.0f;
     }
 }
 
@@ -113,15 +132,16 @@ __device__ __forceinline__ double prob_of(float x, double T, double m, double Z)
 // LOGITS mode: per (row, chunk) max of z/T and sum of exp(z/T - max), fp64.
 // grid = (n_chunks, R_t_cap + R_d_cap)
 // ---------------------------------------------------------------------------------------
+template <typename RT>
 __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
-    const float* __restrict__ z_target, const float* __restrict__ z_draft, const int32_t* __restrict__ cu_t,
+    const RT* __restrict__ z_target, const RT* __restrict__ z_draft, const int32_t* __restrict__ cu_t,
     const int32_t* __restrict__ cu_d, const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows,
     Workspace ws, int B, int V, int R_t_cap, double T) {
     __shared__ double smem[kThreads / 64];
     __shared__ float smax[kThreads / 64];
     const int c = blockIdx.x, nc = gridDim.x;
     int r = blockIdx.y;
-    const float* rows;
+    const RT* rows;
     double* stat;
     if (r < R_t_cap) {
         if (r >= cu_t[B]) return;
@@ -133,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
         rows = z_draft + (size_t)(d_rows ? d_rows[r] : r) * V;
         stat = ws.stat_d + ((size_t)r * nc + c) * 2;
     }
-    const bool vec = ((uintptr_t)rows & 15) == 0;
+    const bool vec = row_vec_ok(rows);
     const int e0 = c * kChunk;
     float vals[kPerThread];
     float mx = -INFINITY;
@@ -180,9 +200,9 @@ __device__ __forceinline__ void combine_stats(const double* __restrict__ stat, i
 // ---------------------------------------------------------------------------------------
 // decide: one wave per request runs the accept tests in order.
 // ---------------------------------------------------------------------------------------
-template <int MODE>
+template <int MODE, typename RT>
 __global__ __launch_bounds__(64) void accept_decide_kernel(
-    const float* __restrict__ p_target, const float* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
+    const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
     const float* __restrict__ u_accept, const int32_t* __restrict__ cu_t, const int32_t* __restrict__ cu_d,
     const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows, int32_t* __restrict__ accepted_len,
     int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
@@ -220,8 +240,8 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
             combine_stats(ws.stat_t + (size_t)(t0 + n) * nc * 2, nc, m_t, Z_t);
             combine_stats(ws.stat_d + (size_t)(d0 + n) * nc * 2, nc, m_d, Z_d);
         }
-        const double px = prob_of<MODE>(p_target[(size_t)tr * V + x], T, m_t, Z_t);
-        const double qx = prob_of<MODE>(p_draft[(size_t)dr * V + x], T, m_d, Z_d);
+        const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t);
+        const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d);
         if (u * qx < px) {
             if (lane == 0) em[n] = x;
             ++n;
@@ -249,9 +269,9 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
 }
 
 // Masses of 4 consecutive tokens starting at e for the request's decision.
-template <int MODE>
-__device__ __forceinline__ void quad_masses(const Decision& dec, const float* __restrict__ trow,
-                                            const float* __restrict__ drow, int e, int V, bool vec_t, bool vec_d,
+template <int MODE, typename RT>
+__device__ __forceinline__ void quad_masses(const Decision& dec, const RT* __restrict__ trow,
+                                            const RT* __restrict__ drow, int e, int V, bool vec_t, bool vec_d,
                                             double T, double (&res)[4], double (&tgt)[4]) {
     float a[4], b[4];
     load_quad(trow, e, V, vec_t, a);
@@ -274,24 +294,24 @@ __device__ __forceinline__ void quad_masses(const Decision& dec, const float* __
 // ---------------------------------------------------------------------------------------
 // partials: fp64 mass of chunk c of request i's sampling distribution.  grid = (n_chunks, B)
 // ---------------------------------------------------------------------------------------
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void accept_partials_kernel(const float* __restrict__ p_target,
-                                                                  const float* __restrict__ p_draft, Workspace ws,
+template <int MODE, typename RT>
+__global__ __launch_bounds__(kThreads) void accept_partials_kernel(const RT* __restrict__ p_target,
+                                                                  const RT* __restrict__ p_draft, Workspace ws,
                                                                   int V, double T) {
     __shared__ double smem[kThreads / 64];
     const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
     const Decision dec = ws.dec[i];
     if (dec.kind == kCaseNone) return;
-    const float* trow = p_target + (size_t)dec.t_row * V;
-    const float* drow = p_draft + (size_t)dec.d_row * V;
-    const bool vec_t = ((uintptr_t)trow & 15) == 0, vec_d = ((uintptr_t)drow & 15) == 0;
+    const RT* trow = p_target + (size_t)dec.t_row * V;
+    const RT* drow = p_draft + (size_t)dec.d_row * V;
+    const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
     const int e0 = c * kChunk;
     double sr = 0.0, st = 0.0;
 #pragma unroll
     for (int k = 0; k < kPerThread / 4; ++k) {
         const int e = e0 + (k * kThreads + threadIdx.x) * 4;
         double res[4], tgt[4];
-        quad_masses<MODE>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
+        quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
         sr += (res[0] + res[1]) + (res[2] + res[3]);
         st += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
     }
@@ -306,9 +326,9 @@ __global__ __launch_bounds__(kThreads) void accept_partials_kernel(const float* 
 // ---------------------------------------------------------------------------------------
 // select: inverse CDF.  grid = (B)
 // ---------------------------------------------------------------------------------------
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void accept_select_kernel(const float* __restrict__ p_target,
-                                                                const float* __restrict__ p_draft,
+template <int MODE, typename RT>
+__global__ __launch_bounds__(kThreads) void accept_select_kernel(const RT* __restrict__ p_target,
+                                                                const RT* __restrict__ p_draft,
                                                                 const float* __restrict__ u_sample,
                                                                 int32_t* __restrict__ n_emitted,
                                                                 int32_t* __restrict__ emitted, Workspace ws, int V,
@@ -368,16 +388,16 @@ __global__ __launch_bounds__(kThreads) void accept_select_kernel(const float* __
     const int c = s_chunk;
 
     // 2. scan inside the chunk: thread t owns tokens [16 t, 16 t + 16) of the chunk
-    const float* trow = p_target + (size_t)dec.t_row * V;
-    const float* drow = p_draft + (size_t)dec.d_row * V;
-    const bool vec_t = ((uintptr_t)trow & 15) == 0, vec_d = ((uintptr_t)drow & 15) == 0;
+    const RT* trow = p_target + (size_t)dec.t_row * V;
+    const RT* drow = p_draft + (size_t)dec.d_row * V;
+    const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
     const int e0 = c * kChunk + threadIdx.x * kPerThread;
     double mass[kPerThread];
     double local = 0.0;
 #pragma unroll
     for (int k = 0; k < kPerThread / 4; ++k) {
         double res[4], tgt[4];
-        quad_masses<MODE>(dec, trow, drow, e0 + 4 * k, V, vec_t, vec_d, T, res, tgt);
+        quad_masses<MODE, RT>(dec, trow, drow, e0 + 4 * k, V, vec_t, vec_d, T, res, tgt);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             mass[4 * k + j] = res[j];
@@ -416,8 +436,8 @@ __global__ __launch_bounds__(kThreads) void accept_select_kernel(const float* __
     }
 }
 
-template <int MODE>
-int launch_all(const float* p_target, const float* p_draft, const int32_t* draft_tokens, const float* u_accept,
+template <int MODE, typename RT>
+int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_tokens, const float* u_accept,
                const float* u_sample, const int32_t* cu_t, const int32_t* cu_d, const int32_t* t_rows,
                const int32_t* d_rows, int32_t* accepted_len, int32_t* n_emitted, int32_t* emitted,
                const fsr_accept_params& p, const Workspace& ws, hipStream_t s) {
@@ -426,24 +446,26 @@ int launch_all(const float* p_target, const float* p_draft, const int32_t* draft
     int rc;
     if (MODE == FSR_LOGITS) {
         const int R_t_cap = p.B * (p.S_max + 1), R_d_cap = p.B * p.S_max;
-        hipLaunchKernelGGL(accept_stats_kernel, dim3(nc, R_t_cap + R_d_cap), dim3(kThreads), 0, s, p_target, p_draft, cu_t,
+        hipLaunchKernelGGL(accept_stats_kernel<RT>, dim3(nc, R_t_cap + R_d_cap), dim3(kThreads), 0, s, p_target, p_draft, cu_t,
                            cu_d, t_rows, d_rows, ws, p.B, p.V, R_t_cap, T);
         if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
     }
-    hipLaunchKernelGGL(accept_decide_kernel<MODE>, dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
+    hipLaunchKernelGGL((accept_decide_kernel<MODE, RT>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
                        cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T);
     if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
-    hipLaunchKernelGGL(accept_partials_kernel<MODE>, dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, ws, p.V, T);
+    hipLaunchKernelGGL((accept_partials_kernel<MODE, RT>), dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, ws, p.V, T);
     if ((rc = check_launch("accept_partials_kernel")) != FSR_OK) return rc;
-    hipLaunchKernelGGL(accept_select_kernel<MODE>, dim3(p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
+    hipLaunchKernelGGL((accept_select_kernel<MODE, RT>), dim3(p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
                        emitted, ws, p.V, p.S_max, T);
     return check_launch("accept_select_kernel");
 }
 
 int validate(const fsr_accept_params* p, const char* who) {
     if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
-    if (p->B < 0 || p->V <= 0 || p->S_max < 0 || p->reserved != 0 || p->reserved2 != 0)
-        return fail(FSR_EINVAL, "%s: B=%d V=%d S_max=%d reserved=%d", who, p->B, p->V, p->S_max, p->reserved);
+    if (p->B < 0 || p->V <= 0 || p->S_max < 0 || p->reserved2 != 0)
+        return fail(FSR_EINVAL, "%s: B=%d V=%d S_max=%d reserved2=%d", who, p->B, p->V, p->S_max, p->reserved2);
+    if (p->dtype != FSR_F32 && p->dtype != FSR_BF16) return fail(FSR_EUNSUP, "%s: dtype=%d", who, p->dtype);
+    if (p->dtype == FSR_BF16 && p->mode == FSR_GREEDY) return fail(FSR_EUNSUP, "%s: greedy mode takes fp32 rows", who);
     if (p->mode != FSR_PROBS && p->mode != FSR_LOGITS && p->mode != FSR_GREEDY) return fail(FSR_EUNSUP, "%s: mode=%d", who, p->mode);
     if (p->mode == FSR_LOGITS && !(p->temperature > 0.0)) return fail(FSR_EINVAL, "%s: temperature=%g must be > 0", who, p->temperature);
     if ((long long)p->B * (2LL * p->S_max + 1) > 65535) return fail(FSR_EUNSUP, "%s: B*(2*S_max+1)=%lld exceeds 65535 rows per call", who, (long long)p->B * (2LL * p->S_max + 1));
@@ -463,7 +485,7 @@ extern "C" int fsr_accept_workspace_bytes(const fsr_accept_params* p, size_t* ou
     return FSR_OK;
 }
 
-extern "C" int fsr_spec_accept(const float* p_target, const float* p_draft, const int32_t* draft_tokens,
+extern "C" int fsr_spec_accept(const void* p_target, const void* p_draft, const int32_t* draft_tokens,
                                const float* u_accept, const float* u_sample, const int32_t* cu_t, const int32_t* cu_d,
                                const int32_t* t_rows, const int32_t* d_rows, int32_t* accepted_len, int32_t* n_emitted,
                                int32_t* emitted, const fsr_accept_params* p, void* workspace, size_t ws_bytes,
@@ -478,7 +500,7 @@ extern "C" int fsr_spec_accept(const float* p_target, const float* p_draft, cons
         const size_t need_g = greedy_workspace_bytes(*p);
         if (!workspace || ws_bytes < need_g) return fail(FSR_EWS, "fsr_spec_accept: workspace %zu bytes, need %zu", ws_bytes, need_g);
         if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "fsr_spec_accept: workspace must be 256-byte aligned");
-        return greedy_accept_launch(p_target, draft_tokens, cu_t, cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, *p,
+        return greedy_accept_launch((const float*)p_target, draft_tokens, cu_t, cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, *p,
                                     workspace, (hipStream_t)stream);
     }
     if (!p_target || !u_sample || !cu_t || !cu_d || !accepted_len || !n_emitted || !emitted)
@@ -492,9 +514,20 @@ extern "C" int fsr_spec_accept(const float* p_target, const float* p_draft, cons
     hipStream_t s = (hipStream_t)stream;
     // a request without drafts never dereferences the draft arrays; give the kernels a valid base
     if (!p_draft) p_draft = p_target;
+    if (p->dtype == FSR_BF16) {
+        const uint16_t* pt = (const uint16_t*)p_target;
+        const uint16_t* pd = (const uint16_t*)p_draft;
+        if (p->mode == FSR_LOGITS)
+            return launch_all<FSR_LOGITS>(pt, pd, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows, accepted_len,
+                                          n_emitted, emitted, *p, ws, s);
+        return launch_all<FSR_PROBS>(pt, pd, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows, accepted_len,
+                                     n_emitted, emitted, *p, ws, s);
+    }
+    const float* pt = (const float*)p_target;
+    const float* pd = (const float*)p_draft;
     if (p->mode == FSR_LOGITS)
-        return launch_all<FSR_LOGITS>(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows,
-                                      accepted_len, n_emitted, emitted, *p, ws, s);
-    return launch_all<FSR_PROBS>(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows,
-                                 accepted_len, n_emitted, emitted, *p, ws, s);
+        return launch_all<FSR_LOGITS>(pt, pd, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows, accepted_len,
+                                      n_emitted, emitted, *p, ws, s);
+    return launch_all<FSR_PROBS>(pt, pd, draft_tokens, u_accept, u_sample, cu_t, cu_d, t_rows, d_rows, accepted_len,
+                                 n_emitted, emitted, *p, ws, s);
 }

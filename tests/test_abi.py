@@ -61,7 +61,7 @@ def test_host_detectable_errors(lib):
     one = ctypes.c_void_p(256)  # never dereferenced: the workspace check comes first
     assert lib.fsr_verify_attention(one, one, one, one, one, None, one, one, None, ctypes.byref(ok), None,
                                     ctypes.c_size_t(0), None) == -4
-    acc = b.AcceptParams(B=4, V=0, S_max=2, mode=0, temperature=1.0, reserved=0, reserved2=0)
+    acc = b.AcceptParams(B=4, V=0, S_max=2, mode=0, temperature=1.0, dtype=0, reserved2=0)
     assert lib.fsr_accept_workspace_bytes(ctypes.byref(acc), ctypes.byref(out)) == -1
     acc.V = 1000; acc.mode = 7
     assert lib.fsr_accept_workspace_bytes(ctypes.byref(acc), ctypes.byref(out)) == -3

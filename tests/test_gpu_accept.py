@@ -134,3 +134,23 @@ def test_invalid_request_is_flagged_not_faulted(fsr, oracle):
     torch.cuda.synchronize()
     acc = acc.cpu().numpy()
     assert (acc[b.spec_lens > 2] == -1).all() and (acc[b.spec_lens <= 2] >= 0).all()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("V", [1000, 20011])
+def test_bf16_rows(fsr, oracle, mode, V):
+    """Probabilities / logits stored as bf16: same decisions as the oracle reading the same bits."""
+    announce(f"accept bf16 rows mode={mode} V={V}")
+    b = workloads.make_batch(2, rep=7, with_kv=False, V=V, B=12, spec_lens=[0, 1, 2, 3, 4, 5, 6, 7, 8, 2, 4, 1],
+                             ctx_lens=[10] * 12, keep_logits=True)
+    src_t, src_d = (b.z_target, b.z_draft) if mode else (b.p_target, b.p_draft)
+    bits_t, bits_d = workloads.f32_to_bf16_bits(src_t), workloads.f32_to_bf16_bits(src_d)
+    kw = dict(S_max=b.S_max, mode=mode, temperature=0.9)
+    ref = oracle.spec_accept(bits_t, bits_d, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d, dtype="bf16", **kw)
+    gpu = fsr.spec_accept(dev(bits_t, True), dev(bits_d, True), dev(b.draft_tokens), dev(b.u_accept), dev(b.u_sample),
+                          dev(b.cu_q), dev(b.cu_d), **kw)
+    torch.cuda.synchronize()
+    frag, mism = check_accept(gpu, ref, b.u_sample)
+    print(f"bf16 rows mode={mode} V={V}: fragile={frag} mismatches={mism}")
+    assert mism <= frag
+    assert 0 < ref["accepted_len"].sum() < b.N_d

@@ -261,3 +261,19 @@ def test_logits_mode_matches_library_softmax(oracle):
         assert r["accepted_len"][i] == n
         assert r["emitted"][i, n] == tok, (i, r["emitted"][i], tok)
     assert 0 < n_rej < B
+
+
+@pytest.mark.parametrize("mode", ["probs", "logits"])
+def test_bf16_rows_equal_their_widened_fp32_rows(oracle, mode):
+    """Rows given as bf16 bit patterns are read as the fp32 values with the same leading bits: the
+    result must be that of the (separately pinned) fp32 path on the widened rows."""
+    b = workloads.make_batch(1, rep=17, keep_logits=True, draft_mode="noise")
+    src_t, src_d = (b.p_target, b.p_draft) if mode == "probs" else (b.z_target, b.z_draft)
+    bits_t, bits_d = workloads.f32_to_bf16_bits(src_t), workloads.f32_to_bf16_bits(src_d)
+    wide_t, wide_d = workloads.bf16_bits_to_f32(bits_t), workloads.bf16_bits_to_f32(bits_d)
+    kw = dict(S_max=b.S_max, mode=oracle.PROBS if mode == "probs" else oracle.LOGITS, temperature=0.8)
+    ref = oracle.spec_accept(wide_t, wide_d, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d, **kw)
+    got = oracle.spec_accept(bits_t, bits_d, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d, dtype="bf16", **kw)
+    for k in ("accepted_len", "n_emitted", "emitted"):
+        assert np.array_equal(ref[k], got[k]), k
+    assert np.array_equal(ref["cdf_lo"], got["cdf_lo"], equal_nan=True)
