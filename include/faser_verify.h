@@ -46,6 +46,8 @@ extern "C" {
 
 enum { FSR_F32 = 0, FSR_BF16 = 1 };
 enum { FSR_PROBS = 0, FSR_LOGITS = 1, FSR_GREEDY = 2 };
+/* layout of a KV cache page: [H_kv][P][D] (one contiguous block per head) or [P][H_kv][D] (one per token) */
+enum { FSR_KV_HEAD_MAJOR = 0, FSR_KV_TOKEN_MAJOR = 1 };
 
 /* Static shape of one attention call. */
 typedef struct fsr_attn_params {
@@ -68,6 +70,8 @@ typedef struct fsr_attn_params {
                           many -- for a call enqueued on a stream that owns only part of the
                           device (Sec. 3.3: drafting and verification share the GPU spatially), so
                           that the persistent grid matches the compute units it will get. */
+    int32_t kv_layout; /* FSR_KV_HEAD_MAJOR: caches are [n_pages, H_kv, P, D];
+                          FSR_KV_TOKEN_MAJOR: caches are [n_pages, P, H_kv, D] */
 } fsr_attn_params;
 
 /* Static shape of one accept call. */
@@ -127,7 +131,7 @@ int fsr_attn_workspace_bytes(const fsr_attn_params* p /*host*/, size_t* out_byte
  * t % P.
  *
  *   q            [N_cap, H_q, D]      dtype
- *   k_cache      [n_pages, H_kv, P, D] dtype       v_cache likewise
+ *   k_cache      [n_pages, H_kv, P, D] dtype, or [n_pages, P, H_kv, D] (kv_layout)   v_cache likewise
  *   block_tables [B, max_pages] int32 (entries beyond a request's last page are not read)
  *   ctx_lens     [B] int32   tokens cached BEFORE this call's first row of the request
  *   spec_lens    [B] int32   nullable, carried for the caller's bookkeeping; cu_q decides

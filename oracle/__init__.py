@@ -59,9 +59,14 @@ def n_threads() -> int:
     return os.cpu_count() or 1
 
 
-def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, H_q, H_kv, D, P, dtype, scale):
-    """Sec. 2.1 verification attention over the paged cache; returns (out[N,H_q,D], lse[N,H_q]) in fp64."""
+def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, H_q, H_kv, D, P, dtype, scale,
+                     token_major=False):
+    """Sec. 2.1 verification attention over the paged cache; returns (out[N,H_q,D], lse[N,H_q]) in fp64.
+    Caches are [n_pages, H_kv, P, D]; with token_major they are [n_pages, P, H_kv, D], which is the same
+    cache with two axes swapped and is handled as exactly that."""
     lib = _load()
+    if token_major:
+        k_cache, v_cache = np.swapaxes(k_cache, 1, 2), np.swapaxes(v_cache, 1, 2)
     code = BF16 if dtype == "bf16" else F32
     st = np.uint16 if code == BF16 else np.float32
     q, k_cache, v_cache = _c(q, st), _c(k_cache, st), _c(v_cache, st)
@@ -182,9 +187,14 @@ def prune_restore(compact, dst_row, *, pad_byte=0):
     return out.view(comp.dtype).reshape((N,) + row_shape), has
 
 
-def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, P):
+def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, P, token_major=False):
     """Store this call's key / value rows ([N, H_kv, D]) into copies of the paged caches
-    ([n_pages, H_kv, P, D]) at positions ctx_lens[i] + j; returns the two new caches."""
+    ([n_pages, H_kv, P, D]; [n_pages, P, H_kv, D] with token_major) at positions ctx_lens[i] + j; returns
+    the two new caches in the layout they came in."""
+    if token_major:
+        kc, vc = kv_append(k_new, v_new, np.swapaxes(k_cache, 1, 2), np.swapaxes(v_cache, 1, 2), block_tables, ctx_lens,
+                           cu_q, P=P)
+        return np.ascontiguousarray(np.swapaxes(kc, 1, 2)), np.ascontiguousarray(np.swapaxes(vc, 1, 2))
     lib = _load()
     kc, vc = np.array(k_cache, copy=True, order="C"), np.array(v_cache, copy=True, order="C")
     kn, vn = np.ascontiguousarray(k_new), np.ascontiguousarray(v_new)

@@ -18,6 +18,7 @@ _lib = None
 
 F32, BF16 = 0, 1
 PROBS, LOGITS, GREEDY = 0, 1, 2
+KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
 
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_kv_append",
@@ -35,7 +36,8 @@ class FsrError(RuntimeError):
 class AttnParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "N_cap", "H_q", "H_kv", "D", "P", "max_pages", "n_pages", "dtype", "out_dtype")] + \
-               [("scale", ctypes.c_float), ("max_q_len", ctypes.c_int32), ("max_workgroups", ctypes.c_int32)]
+               [("scale", ctypes.c_float), ("max_q_len", ctypes.c_int32), ("max_workgroups", ctypes.c_int32),
+                ("kv_layout", ctypes.c_int32)]
 
 
 class AcceptParams(ctypes.Structure):
@@ -110,34 +112,39 @@ def _code(dt: torch.dtype) -> int:
     raise ValueError(f"unsupported dtype {dt}")
 
 
-def _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len, max_workgroups=0) -> AttnParams:
+def _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len, max_workgroups=0,
+                 kv_layout=KV_HEAD_MAJOR) -> AttnParams:
     N_cap, H_q, D = q.shape
-    n_pages, H_kv, P, D2 = k_cache.shape
+    if kv_layout == KV_TOKEN_MAJOR:
+        n_pages, P, H_kv, D2 = k_cache.shape
+    else:
+        n_pages, H_kv, P, D2 = k_cache.shape
     if D2 != D:
         raise ValueError("head dim of q and k_cache differ")
     return AttnParams(B=B, N_cap=N_cap, H_q=H_q, H_kv=H_kv, D=D, P=P, max_pages=block_tables.shape[1],
                       n_pages=n_pages, dtype=_code(q.dtype), out_dtype=_code(out_dtype), scale=float(scale),
-                      max_q_len=int(max_q_len), max_workgroups=int(max_workgroups))
+                      max_q_len=int(max_q_len), max_workgroups=int(max_workgroups), kv_layout=int(kv_layout))
 
 
 def attn_workspace_bytes(*, B, N_cap, H_q, H_kv, D, P, max_pages, n_pages, dtype, out_dtype, scale=1.0,
                          max_q_len=0) -> int:
     p = AttnParams(B=B, N_cap=N_cap, H_q=H_q, H_kv=H_kv, D=D, P=P, max_pages=max_pages, n_pages=n_pages,
                    dtype=_code(dtype), out_dtype=_code(out_dtype), scale=float(scale), max_q_len=int(max_q_len),
-                   max_workgroups=0)
+                   max_workgroups=0, kv_layout=0)
     out = ctypes.c_size_t(0)
     _check(load_library().fsr_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
     return int(out.value)
 
 
 def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_q, *, scale, out=None, lse=None,
-                     out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0):
+                     out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR):
     """fsr_verify_attention.  q [N_cap,H_q,D]; caches [n_pages,H_kv,P,D]; returns (out, lse).
-    max_workgroups: size of the persistent grid when the current stream owns only part of the device."""
+    max_workgroups: size of the persistent grid when the current stream owns only part of the device.
+    kv_layout: KV_HEAD_MAJOR (caches [n_pages,H_kv,P,D]) or KV_TOKEN_MAJOR (caches [n_pages,P,H_kv,D])."""
     lib = load_library()
     B = ctx_lens.shape[0]
     out_dtype = out_dtype or (out.dtype if out is not None else q.dtype)
-    p = _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len, max_workgroups)
+    p = _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len, max_workgroups, kv_layout)
     if out is None:
         out = torch.empty(q.shape, dtype=out_dtype, device=q.device)
     if v_cache.shape != k_cache.shape or v_cache.dtype != k_cache.dtype or k_cache.dtype != q.dtype:
@@ -158,18 +165,21 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
     return out, lse
 
 
-def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q):
+def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, kv_layout=KV_HEAD_MAJOR):
     """fsr_kv_append: store the call's key / value rows [N_cap, H_kv, D] into the paged caches (in place)."""
     lib = load_library()
     B = ctx_lens.shape[0]
-    n_pages, H_kv, P, D = k_cache.shape
+    if kv_layout == KV_TOKEN_MAJOR:
+        n_pages, P, H_kv, D = k_cache.shape
+    else:
+        n_pages, H_kv, P, D = k_cache.shape
     if k_new.shape != v_new.shape or k_new.shape[1:] != (H_kv, D) or v_cache.shape != k_cache.shape:
         raise ValueError("k_new/v_new must be [N_cap, H_kv, D] matching the caches")
     if not (k_new.dtype == v_new.dtype == k_cache.dtype == v_cache.dtype):
         raise ValueError("k_new, v_new and the caches must share a dtype")
     p = AttnParams(B=B, N_cap=k_new.shape[0], H_q=H_kv, H_kv=H_kv, D=D, P=P, max_pages=block_tables.shape[1],
                    n_pages=n_pages, dtype=_code(k_new.dtype), out_dtype=_code(k_new.dtype), scale=1.0, max_q_len=0,
-                   max_workgroups=0)
+                   max_workgroups=0, kv_layout=int(kv_layout))
     _check(lib.fsr_kv_append(_ptr(k_new, name="k_new"), _ptr(v_new, name="v_new"), _ptr(k_cache, name="k_cache"),
                              _ptr(v_cache, name="v_cache"), _ptr(block_tables, torch.int32, "block_tables"),
                              _ptr(ctx_lens, torch.int32, "ctx_lens"), _ptr(cu_q, torch.int32, "cu_q"), ctypes.byref(p),

@@ -25,6 +25,7 @@ struct AppendArgs {
     const int32_t* ctx;
     const int32_t* cu_q;
     int B, N_cap, H_kv, P, max_pages, n_pages;
+    int token_major;  // 1: caches are [page][P][H_kv][D], 0: [page][H_kv][P][D]
     int vec_bytes;  // D * element size, a multiple of 16
 };
 
@@ -50,7 +51,8 @@ __global__ __launch_bounds__(kThreads) void kv_append_kernel(AppendArgs a) {
     const int page = a.bt[(size_t)i * a.max_pages + t / a.P];
     if (page < 0 || page >= a.n_pages) return;                  // never write outside the pool
     const size_t src = ((size_t)row * a.H_kv + g) * a.vec_bytes + (size_t)part * 16;
-    const size_t dst = (((size_t)page * a.H_kv + g) * a.P + t % a.P) * a.vec_bytes + (size_t)part * 16;
+    const size_t slot = a.token_major ? ((size_t)page * a.P + t % a.P) * a.H_kv + g : ((size_t)page * a.H_kv + g) * a.P + t % a.P;
+    const size_t dst = slot * a.vec_bytes + (size_t)part * 16;
     *reinterpret_cast<u32x4*>(a.k_cache + dst) = *reinterpret_cast<const u32x4*>(a.k_new + src);
     *reinterpret_cast<u32x4*>(a.v_cache + dst) = *reinterpret_cast<const u32x4*>(a.v_new + src);
 }
@@ -68,6 +70,7 @@ extern "C" int fsr_kv_append(const void* k_new, const void* v_new, void* k_cache
         return fail(FSR_EINVAL, "fsr_kv_append: B=%d N_cap=%d H_kv=%d D=%d P=%d max_pages=%d n_pages=%d", p->B, p->N_cap,
                     p->H_kv, p->D, p->P, p->max_pages, p->n_pages);
     if (p->dtype != FSR_F32 && p->dtype != FSR_BF16) return fail(FSR_EUNSUP, "fsr_kv_append: dtype=%d", p->dtype);
+    if (p->kv_layout != FSR_KV_HEAD_MAJOR && p->kv_layout != FSR_KV_TOKEN_MAJOR) return fail(FSR_EINVAL, "fsr_kv_append: kv_layout=%d", p->kv_layout);
     const int vec_bytes = p->D * (p->dtype == FSR_F32 ? 4 : 2);
     if (vec_bytes % 16 != 0) return fail(FSR_EUNSUP, "fsr_kv_append: D=%d gives %d-byte vectors, need a multiple of 16", p->D, vec_bytes);
     if (p->B == 0 || p->N_cap == 0) return FSR_OK;
@@ -80,6 +83,7 @@ extern "C" int fsr_kv_append(const void* k_new, const void* v_new, void* k_cache
     a.bt = block_tables; a.ctx = ctx_lens; a.cu_q = cu_q;
     a.B = p->B; a.N_cap = p->N_cap; a.H_kv = p->H_kv; a.P = p->P; a.max_pages = p->max_pages; a.n_pages = p->n_pages;
     a.vec_bytes = vec_bytes;
+    a.token_major = p->kv_layout == FSR_KV_TOKEN_MAJOR;
     const long long pieces = (long long)p->N_cap * p->H_kv * (vec_bytes / 16);
     const long long blocks = (pieces + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return fail(FSR_EUNSUP, "fsr_kv_append: N_cap * H_kv * D too large for one launch");

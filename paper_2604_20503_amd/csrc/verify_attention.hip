@@ -257,13 +257,23 @@ __device__ __forceinline__ const const_i32* uniform(const const_i32* p) {
     return (const const_i32*)(((unsigned long long)hi << 32) | lo);
 }
 
+// Cache layouts.  TM = false: a page holds one [P, D] block per KV head (keys of a head 256 bytes
+// apart, heads 4 KB apart).  TM = true: a page holds one [H_kv, D] block per token (keys of a head
+// H_kv * 256 bytes apart, heads 256 bytes apart).  A template parameter, so that the first layout
+// keeps every offset as an instruction immediate.
+template <bool TM>
+__device__ __forceinline__ int key_stride(const FastArgs& a) { return TM ? a.H_kv * kD * 2 : kD * 2; }
+template <bool TM>
+__device__ __forceinline__ int head_stride() { return TM ? kD * 2 : kP * kD * 2; }
+
+template <bool TM>
 __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment& sg) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     KVStream st;
     st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
-    st.k_head = reinterpret_cast<const char*>(a.k) + (size_t)kvh * kP * kD * 2;
-    st.v_head = reinterpret_cast<const char*>(a.v) + (size_t)kvh * kP * kD * 2;
+    st.k_head = reinterpret_cast<const char*>(a.k) + (size_t)kvh * head_stride<TM>();
+    st.v_head = reinterpret_cast<const char*>(a.v) + (size_t)kvh * head_stride<TM>();
     const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
     st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
     const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
@@ -339,6 +349,7 @@ struct ShareWalker {
     }
 };
 
+template <bool TM>
 __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, KVTile& t, int ti) {
     const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
     KVStream st;
@@ -349,8 +360,9 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     const int kb = st.kb0 + min(ti, st.nw - 1) * kStep;
     // per-lane byte offsets inside a 4 KB (page, head) block: every load is then
     // "uniform base + this offset + immediate", with no per-load address arithmetic
-    const int kl = real ? li * 256 + lg * 16 : 0;  // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
-    const int vl = real ? lg * 256 + li * 16 : 0;  // V: key lg (+ 4 r), 16-byte chunk li
+    const int ks = key_stride<TM>(a);
+    const int kl = real ? li * ks + lg * 16 : 0;  // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
+    const int vl = real ? lg * ks + li * 16 : 0;  // V: key lg (+ 4 r), 16-byte chunk li
     const size_t page_bytes = (size_t)a.H_kv * kP * kD * 2;
     // the second page exists only if the request has tokens there
     int pg0 = st.bt[kb >> 4];
@@ -369,13 +381,13 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        t.v[r] = *reinterpret_cast<const s16x8*>(vp0 + vl + 1024 * r);
-        t.v[4 + r] = *reinterpret_cast<const s16x8*>(vp1 + vl + 1024 * r);
+        t.v[r] = *reinterpret_cast<const s16x8*>(vp0 + vl + 4 * ks * r);
+        t.v[4 + r] = *reinterpret_cast<const s16x8*>(vp1 + vl + 4 * ks * r);
     }
 }
 
 // Process one segment: stream the wave's tiles, merge the 4 waves, write the result or the partial.
-template <int MT>
+template <int MT, bool TM>
 __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem, int seg_no) {
     FSR_STAMP(seg_no * 5 + 2);
     // everything that is the same for the whole wave goes to scalar registers
@@ -403,7 +415,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
 #pragma unroll
         for (int db = 0; db < 8; ++db) vr_off[db] = vtile_off(r0, 2 * db + ((li & 3) >> 1)) + (li & 1) * 8;
     }
-    auto issue = [&](KVTile& t, int ti) { issue_tile(a, st, t, ti); };
+    auto issue = [&](KVTile& t, int ti) { issue_tile<TM>(a, st, t, ti); };
     // The K/V stream does not depend on Q: start it before anything else of the segment.
     // Two tiles in flight per wave.  (A third, where the registers would allow it, does not raise
     // the rate: a compute unit draws only about twice its even share of the HBM bandwidth however
@@ -762,11 +774,11 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
 }
 
-template <int MTMAX>
+template <int MTMAX, bool TM>
 __device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem,
                                                 int seg_no) {
     const int mt = (a.G * sg.rows_g + 15) >> 4;
-#define FSR_SEG(MT) attend_segment<MT>(a, sg, st, smem, seg_no)
+#define FSR_SEG(MT) attend_segment<MT, TM>(a, sg, st, smem, seg_no)
     if constexpr (MTMAX == 1) {
         FSR_SEG(1);
     } else if constexpr (MTMAX == 2) {
@@ -873,7 +885,7 @@ __device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned 
 // inside one share is finished by that workgroup; an item cut by share boundaries leaves one
 // partial per piece, and the workgroup whose piece arrives last combines them (no workgroup ever
 // waits for another).
-template <int MTMAX>
+template <int MTMAX, bool TM>
 __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
@@ -902,8 +914,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     Segment cur;
     int seg_no = 0;
     while (wk.next(a, cur)) {
-        const KVStream st = make_stream(a, cur);
-        attend_dispatch<MTMAX>(a, cur, st, smem, min(seg_no, 2));
+        const KVStream st = make_stream<TM>(a, cur);
+        attend_dispatch<MTMAX, TM>(a, cur, st, smem, min(seg_no, 2));
         ++seg_no;
         if (wk.cut) {
             // pieces of this item: the workgroups that own its first .. last tile; workgroup bb owns
@@ -952,6 +964,7 @@ struct GenericArgs {
     void* out;
     float* lse;
     int B, H_q, H_kv, P, max_pages, n_pages;
+    int token_major;  // 1: caches are [page][P][H_kv][D], 0: [page][H_kv][P][D]
     float scale;
 };
 
@@ -985,7 +998,8 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(GenericArgs a) {
     const T* vc = reinterpret_cast<const T*>(a.v);
     for (int t = lane; t < L; t += 64) {
         const int pg = min(max(bt[t / a.P], 0), a.n_pages - 1);
-        const size_t base = (((size_t)pg * a.H_kv + g) * a.P + t % a.P) * D;
+        const size_t base = a.token_major ? (((size_t)pg * a.P + t % a.P) * a.H_kv + g) * D
+                                          : (((size_t)pg * a.H_kv + g) * a.P + t % a.P) * D;
         float s = 0.0f;
 #pragma unroll
         for (int d = 0; d < D; ++d) s = fmaf(qs[d], to_f32<T>(kc[base + d]), s);
@@ -1027,9 +1041,10 @@ struct Plan {
 int validate(const fsr_attn_params* p, const char* who) {
     if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
     if (p->max_q_len < 0) return fail(FSR_EINVAL, "%s: max_q_len=%d", who, p->max_q_len);
-    if (p->B < 0 || p->N_cap < 0 || p->H_q <= 0 || p->H_kv <= 0 || p->max_pages <= 0 || p->n_pages <= 0 || p->P <= 0 || p->max_workgroups < 0)
-        return fail(FSR_EINVAL, "%s: B=%d N_cap=%d H_q=%d H_kv=%d max_pages=%d n_pages=%d P=%d max_workgroups=%d", who, p->B, p->N_cap,
-                    p->H_q, p->H_kv, p->max_pages, p->n_pages, p->P, p->max_workgroups);
+    if (p->B < 0 || p->N_cap < 0 || p->H_q <= 0 || p->H_kv <= 0 || p->max_pages <= 0 || p->n_pages <= 0 || p->P <= 0 || p->max_workgroups < 0 ||
+        (p->kv_layout != FSR_KV_HEAD_MAJOR && p->kv_layout != FSR_KV_TOKEN_MAJOR))
+        return fail(FSR_EINVAL, "%s: B=%d N_cap=%d H_q=%d H_kv=%d max_pages=%d n_pages=%d P=%d max_workgroups=%d kv_layout=%d", who, p->B, p->N_cap,
+                    p->H_q, p->H_kv, p->max_pages, p->n_pages, p->P, p->max_workgroups, p->kv_layout);
     if (p->H_q % p->H_kv != 0) return fail(FSR_ESHAPE, "%s: H_q=%d is not a multiple of H_kv=%d", who, p->H_q, p->H_kv);
     if (p->D != 64 && p->D != 128) return fail(FSR_EUNSUP, "%s: head dim %d (64 and 128 are built)", who, p->D);
     if (p->dtype != FSR_F32 && p->dtype != FSR_BF16) return fail(FSR_EUNSUP, "%s: dtype=%d", who, p->dtype);
@@ -1138,18 +1153,25 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
         a.dbg = (long long*)((char*)workspace + need);  // the timing build expects 1 MiB of slack after the workspace
 #endif
         const dim3 grid(pl.nb), block(kThreads);
+#define FSR_LAUNCH(MT)                                                                              \
+    if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                         \
+        hipLaunchKernelGGL((attn_stream_kernel<MT, true>), grid, block, kFastSmem, s, a);           \
+    else                                                                                            \
+        hipLaunchKernelGGL((attn_stream_kernel<MT, false>), grid, block, kFastSmem, s, a)
         switch (pl.mt_max) {
-            case 1: hipLaunchKernelGGL(attn_stream_kernel<1>, grid, block, kFastSmem, s, a); break;
-            case 2: hipLaunchKernelGGL(attn_stream_kernel<2>, grid, block, kFastSmem, s, a); break;
-            case 3: hipLaunchKernelGGL(attn_stream_kernel<3>, grid, block, kFastSmem, s, a); break;
-            default: hipLaunchKernelGGL(attn_stream_kernel<4>, grid, block, kFastSmem, s, a); break;
+            case 1: FSR_LAUNCH(1); break;
+            case 2: FSR_LAUNCH(2); break;
+            case 3: FSR_LAUNCH(3); break;
+            default: FSR_LAUNCH(4); break;
         }
+#undef FSR_LAUNCH
         return check_launch("attn_stream_kernel");
     }
     GenericArgs g;
     g.q = q; g.k = k_cache; g.v = v_cache; g.bt = block_tables; g.ctx = ctx_lens; g.cu_q = cu_q; g.out = out; g.lse = lse;
     g.B = p->B; g.H_q = p->H_q; g.H_kv = p->H_kv; g.P = p->P; g.max_pages = p->max_pages; g.n_pages = p->n_pages;
     g.scale = p->scale;
+    g.token_major = p->kv_layout == FSR_KV_TOKEN_MAJOR;
     const dim3 grid(p->H_q, p->N_cap), block(64);
     if (p->N_cap > 65535) return fail(FSR_EUNSUP, "fsr_verify_attention: generic path is limited to N_cap <= 65535 rows");
     const bool bf_in = p->dtype == FSR_BF16, bf_out = p->out_dtype == FSR_BF16;

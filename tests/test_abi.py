@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header():
     from paper_2604_20503_amd import binding
-    assert ctypes.sizeof(binding.AttnParams) == 13 * 4
+    assert ctypes.sizeof(binding.AttnParams) == 14 * 4
     assert ctypes.sizeof(binding.AcceptParams) == 32 and binding.AcceptParams.temperature.offset == 16
     assert ctypes.sizeof(binding.PruneParams) == 16
     assert ctypes.sizeof(binding.RankParams) == 7 * 4
@@ -45,7 +45,7 @@ def test_host_detectable_errors(lib):
     from paper_2604_20503_amd import binding as b
     out = ctypes.c_size_t(0)
     ok = b.AttnParams(B=2, N_cap=8, H_q=32, H_kv=8, D=128, P=16, max_pages=4, n_pages=16, dtype=1, out_dtype=1,
-                      scale=0.1, max_q_len=4, max_workgroups=0)
+                      scale=0.1, max_q_len=4, max_workgroups=0, kv_layout=0)
     assert lib.fsr_attn_workspace_bytes(ctypes.byref(ok), ctypes.byref(out)) == 0 and out.value > 0
     assert lib.fsr_attn_workspace_bytes(None, ctypes.byref(out)) == -1
     bad = b.AttnParams.from_buffer_copy(ok); bad.H_kv = 5

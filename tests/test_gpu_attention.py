@@ -128,3 +128,45 @@ def test_config2_full_size_and_determinism(fsr, oracle):
     np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
     out2, _ = run_gpu(fsr, b, d, torch.bfloat16, want_lse=False)
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16))  # same bits on a re-run
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_token_major_cache_layout(fsr, oracle, out_dtype):
+    """Caches laid out [n_pages, P, H_kv, D] (one block per token instead of one per head)."""
+    announce(f"attention token-major KV layout out={out_dtype}")
+    ctx = [0, 1, 15, 16, 31, 33, 100, 257, 511, 640, 700, 1029, 2100]
+    spec = [3, 0, 8, 1, 2, 7, 4, 8, 5, 6, 0, 8, 3]
+    b = workloads.make_batch(2, rep=61, with_probs=False, ctx_lens=ctx, spec_lens=spec)
+    k_tm = np.ascontiguousarray(np.swapaxes(b.k_cache, 1, 2))
+    v_tm = np.ascontiguousarray(np.swapaxes(b.v_cache, 1, 2))
+    o_ref, lse_ref = oracle.verify_attention(b.q, k_tm, v_tm, b.block_tables, b.ctx_lens, b.cu_q, H_q=b.H_q, H_kv=b.H_kv,
+                                             D=b.D, P=b.P, dtype=b.dtype, scale=b.scale, token_major=True)
+    d = DeviceBatch(b, probs=False)
+    lse = torch.zeros((b.N, b.H_q), dtype=torch.float32, device="cuda")
+    out, lse = fsr.verify_attention(d.q, dev(k_tm, True), dev(v_tm, True), d.block_tables, d.ctx_lens, d.spec_lens, d.cu_q,
+                                    scale=b.scale, out_dtype=out_dtype, lse=lse, max_q_len=b.S_max + 1, kv_layout=1)
+    torch.cuda.synchronize()
+    check_attention(out, o_ref, "bf16", b.N)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
+
+
+def test_token_major_generic_path_and_append(fsr, oracle):
+    announce("token-major layout: fp32 generic path, and cache append")
+    b = workloads.make_batch(1, rep=9, with_probs=False)
+    k_tm = np.ascontiguousarray(np.swapaxes(b.k_cache, 1, 2))
+    v_tm = np.ascontiguousarray(np.swapaxes(b.v_cache, 1, 2))
+    o_ref, _ = oracle.verify_attention(b.q, k_tm, v_tm, b.block_tables, b.ctx_lens, b.cu_q, H_q=b.H_q, H_kv=b.H_kv, D=b.D,
+                                       P=b.P, dtype=b.dtype, scale=b.scale, token_major=True)
+    d = DeviceBatch(b, probs=False)
+    out, _ = fsr.verify_attention(d.q, dev(k_tm), dev(v_tm), d.block_tables, d.ctx_lens, d.spec_lens, d.cu_q,
+                                  scale=b.scale, out_dtype=torch.float32, max_q_len=b.S_max + 1, kv_layout=1)
+    torch.cuda.synchronize()
+    check_attention(out, o_ref, "f32", b.N)
+    rng = np.random.default_rng(2)
+    k_new = rng.standard_normal((b.N, b.H_kv, b.D)).astype(np.float32)
+    v_new = rng.standard_normal((b.N, b.H_kv, b.D)).astype(np.float32)
+    kc, vc = dev(k_tm), dev(v_tm)
+    fsr.kv_append(dev(k_new), dev(v_new), kc, vc, d.block_tables, d.ctx_lens, d.cu_q, kv_layout=1)
+    torch.cuda.synchronize()
+    kr, vr = oracle.kv_append(k_new, v_new, k_tm, v_tm, b.block_tables, b.ctx_lens, b.cu_q, P=b.P, token_major=True)
+    assert np.array_equal(kc.cpu().numpy(), kr) and np.array_equal(vc.cpu().numpy(), vr)
