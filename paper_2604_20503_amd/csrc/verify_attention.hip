@@ -40,6 +40,10 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(4))) int32_t const_i32;
+// K/V bytes are addressed through the global address space explicitly: a pointer rebuilt from scalar
+// halves is otherwise a generic one, and its loads are "flat" ones that also count as LDS accesses
+typedef const __attribute__((address_space(1))) char gmem_char;
+typedef const __attribute__((address_space(1))) __attribute__((__vector_size__(8 * sizeof(short)))) short gmem_s16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int kD = 128;           // head dim of the fast path
@@ -230,8 +234,8 @@ struct Segment {
 struct KVStream {
     const const_i32* bt;  // the request's block table, read through the constant address space so
                           // that the (wave-uniform) page look-ups are scalar loads
-    const char* k_head;   // caches offset to the KV head
-    const char* v_head;
+    gmem_char* k_head;   // caches offset to the KV head
+    gmem_char* v_head;
     int kb0, nw, kv_total, kend;
 };
 
@@ -250,6 +254,11 @@ __device__ __forceinline__ T* uniform(T* p) {
 __device__ __forceinline__ long long uniform(long long x) {
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)x), hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)x >> 32));
     return (long long)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ gmem_char* uniform(gmem_char* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (gmem_char*)(((unsigned long long)hi << 32) | lo);
 }
 __device__ __forceinline__ const const_i32* uniform(const const_i32* p) {
     const unsigned long long v = (unsigned long long)p;
@@ -272,8 +281,8 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     KVStream st;
     st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
-    st.k_head = reinterpret_cast<const char*>(a.k) + (size_t)kvh * head_stride<TM>();
-    st.v_head = reinterpret_cast<const char*>(a.v) + (size_t)kvh * head_stride<TM>();
+    st.k_head = (gmem_char*)a.k + (size_t)kvh * head_stride<TM>();
+    st.v_head = (gmem_char*)a.v + (size_t)kvh * head_stride<TM>();
     const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
     st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
     const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
@@ -369,20 +378,20 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     int pg1 = (kb + kP < st.kv_total) ? st.bt[(kb >> 4) + 1] : pg0;
     pg0 = min(max(pg0, 0), a.n_pages - 1);
     pg1 = min(max(pg1, 0), a.n_pages - 1);
-    const char* kp0 = st.k_head + (size_t)pg0 * page_bytes;
-    const char* kp1 = st.k_head + (size_t)pg1 * page_bytes;
-    const char* vp0 = st.v_head + (size_t)pg0 * page_bytes;
-    const char* vp1 = st.v_head + (size_t)pg1 * page_bytes;
+    gmem_char* kp0 = st.k_head + (size_t)pg0 * page_bytes;
+    gmem_char* kp1 = st.k_head + (size_t)pg1 * page_bytes;
+    gmem_char* vp0 = st.v_head + (size_t)pg0 * page_bytes;
+    gmem_char* vp1 = st.v_head + (size_t)pg1 * page_bytes;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        t.k[0][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp0 + kl + 64 * kk));
-        t.k[1][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(kp1 + kl + 64 * kk));
+        t.k[0][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp0 + kl + 64 * kk));
+        t.k[1][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp1 + kl + 64 * kk));
     }
     // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        t.v[r] = *reinterpret_cast<const s16x8*>(vp0 + vl + 4 * ks * r);
-        t.v[4 + r] = *reinterpret_cast<const s16x8*>(vp1 + vl + 4 * ks * r);
+        t.v[r] = *(gmem_s16x8*)(vp0 + vl + 4 * ks * r);
+        t.v[4 + r] = *(gmem_s16x8*)(vp1 + vl + 4 * ks * r);
     }
 }
 
