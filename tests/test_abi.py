@@ -18,19 +18,25 @@ def lib():
     return binding.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "faser_verify.h")).read()
+def declared_symbols(header="faser_verify.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fsr_[a-z_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
-    from paper_2604_20503_amd import binding
+    from paper_2604_20503_amd import binding, controller
     names = declared_symbols()
     assert len(names) >= 12
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(binding.SYMBOLS) == names
+    ctl_names = declared_symbols("faser_controller.h")
+    assert len(ctl_names) == 14
+    for n in ctl_names:
+        assert hasattr(lib, n), n
+    assert sorted(controller.CTL_SYMBOLS) == ctl_names
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["faser_controller.h", "faser_verify.h"]
 
 
 def test_struct_layouts_match_header():
@@ -39,6 +45,9 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.AcceptParams) == 32 and binding.AcceptParams.temperature.offset == 16
     assert ctypes.sizeof(binding.PruneParams) == 16
     assert ctypes.sizeof(binding.RankParams) == 7 * 4
+    from paper_2604_20503_amd import controller
+    assert ctypes.sizeof(controller.CtlConfig) == 4 * 19 + 4 + 6 * 8 and controller.CtlConfig.eps.offset == 80
+    assert ctypes.sizeof(controller.LatencyModel) == 8 + 8 * 8
 
 
 def test_host_detectable_errors(lib):
