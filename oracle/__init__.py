@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "faser_oracle.c")
 _LIB = os.path.join(_HERE, "libfaser_oracle.so")
 _lib = None
 
-F32, BF16 = 0, 1
+F32, BF16, F64 = 0, 1, 2
 PROBS, LOGITS, GREEDY = 0, 1, 2
 
 
@@ -79,6 +79,41 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, H_q, 
                                  ctypes.c_int(B), ctypes.c_int(H_q), ctypes.c_int(H_kv), ctypes.c_int(D),
                                  ctypes.c_int(P), ctypes.c_int(bt.shape[1]), ctypes.c_int(code),
                                  ctypes.c_double(scale))
+    if rc != 0:
+        raise ValueError(f"fo_verify_attention: {rc}")
+    return out, lse
+
+
+def decode_e4m3(codes):
+    """Values of OCP E4M3 bytes as fp64 (NaN for the two NaN codes)."""
+    lib = _load()
+    codes = _c(codes, np.uint8)
+    out = np.empty(codes.shape, dtype=np.float64)
+    lib.fo_decode_e4m3(_p(codes), _p(out), ctypes.c_int64(codes.size))
+    return out
+
+
+def verify_attention_kv8(q_bits, k_cache8, v_cache8, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, H_q, H_kv, D, P,
+                         scale, token_major=False):
+    """The same attention with the caches stored as E4M3 bytes: cached key = decode(byte) * k_scale[kv head],
+    cached value = decode(byte) * v_scale[kv head]; queries are bf16 bit patterns.  Everything is widened to
+    fp64 first (exactly), then the plain definition runs."""
+    lib = _load()
+    if token_major:
+        k_cache8, v_cache8 = np.swapaxes(k_cache8, 1, 2), np.swapaxes(v_cache8, 1, 2)
+    ks = np.asarray(k_scale, dtype=np.float32).astype(np.float64).reshape(1, H_kv, 1, 1)
+    vs = np.asarray(v_scale, dtype=np.float32).astype(np.float64).reshape(1, H_kv, 1, 1)
+    k = _c(decode_e4m3(k_cache8) * ks, np.float64)
+    v = _c(decode_e4m3(v_cache8) * vs, np.float64)
+    qb = _c(q_bits, np.uint16)
+    q = _c((qb.astype(np.uint32) << 16).view(np.float32).astype(np.float64), np.float64)
+    bt, ctx, cu = _c(block_tables, np.int32), _c(ctx_lens, np.int32), _c(cu_q, np.int32)
+    N = int(cu[-1])
+    out = np.zeros((N, H_q, D), dtype=np.float64)
+    lse = np.zeros((N, H_q), dtype=np.float64)
+    rc = lib.fo_verify_attention(_p(q), _p(k), _p(v), _p(bt), _p(ctx), _p(cu), _p(out), _p(lse),
+                                 ctypes.c_int(len(ctx)), ctypes.c_int(H_q), ctypes.c_int(H_kv), ctypes.c_int(D),
+                                 ctypes.c_int(P), ctypes.c_int(bt.shape[1]), ctypes.c_int(F64), ctypes.c_double(scale))
     if rc != 0:
         raise ValueError(f"fo_verify_attention: {rc}")
     return out, lse

@@ -50,18 +50,41 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { FO_F32 = 0, FO_BF16 = 1 };
+enum { FO_F32 = 0, FO_BF16 = 1, FO_F64 = 2 };
 enum { FO_PROBS = 0, FO_LOGITS = 1 };
 
 static double load_elem(const void *base, int64_t idx, int dtype)
 {
     if (dtype == FO_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == FO_F64)
+        return ((const double *)base)[idx];
     /* bf16: the upper half of an IEEE fp32 */
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, 4);
     return (double)f;
+}
+
+/*
+ * Value of an 8-bit float in the OCP "E4M3" format (1 sign, 4 exponent bits with bias 7, 3
+ * mantissa bits; no infinities; exponent 15 with mantissa 7 is NaN; exponent 0 is subnormal,
+ * mantissa / 8 * 2^-6).  Used for KV caches stored in 8 bits (a storage variant of the
+ * verification attention: the arithmetic is unchanged, the cached values are value * scale).
+ */
+void fo_decode_e4m3(const uint8_t *codes, double *out, int64_t n)
+{
+    for (int64_t k = 0; k < n; ++k) {
+        const int c = codes[k], e = (c >> 3) & 15, m = c & 7;
+        double v;
+        if (e == 15 && m == 7)
+            v = NAN;
+        else if (e == 0)
+            v = ldexp((double)m / 8.0, -6);
+        else
+            v = ldexp(1.0 + (double)m / 8.0, e - 7);
+        out[k] = (c & 0x80) ? -v : v;
+    }
 }
 
 /*

@@ -39,6 +39,21 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return r
 
 
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to the 8-bit OCP E4M3 format (nearest, ties to the even code; magnitudes above 448, the largest
+    finite value, saturate to it) and return the byte patterns.  Storage format conversion only."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.arange(127)
+    e, m = codes >> 3, codes & 7
+    values = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1 + m / 8.0) * 2.0 ** (e - 7.0))  # codes 0x00 .. 0x7e, increasing
+    mid = (values[:-1] + values[1:]) / 2
+    mag = np.minimum(np.abs(x).astype(np.float64), values[-1])
+    lo = np.searchsorted(mid, mag, side="left")           # mid[lo-1] < mag <= mid[lo]
+    tie = (lo < len(mid)) & (mag == mid[np.minimum(lo, len(mid) - 1)])
+    code = np.where(tie & (lo % 2 == 1), lo + 1, lo).astype(np.uint8)
+    return np.where(np.signbit(x), code | np.uint8(0x80), code).astype(np.uint8)
+
+
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Widen bf16 bit patterns (uint16) to fp32 exactly."""
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
