@@ -150,6 +150,26 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
                          void* stream);
 
 /*
+ * The same attention (Sec. 2.1, Sec. 3.1) over caches stored in 8 bits: every element of k_cache /
+ * v_cache is one byte in the OCP E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
+ * no infinities), and the cached key (value) it stands for is decode(byte) * k_scale[kv head]
+ * (* v_scale[kv head]).  Storage only: queries, softmax and accumulation are as above (the bytes are
+ * widened exactly to bf16 on the way to the matrix cores; the key scale joins the softmax scale, the
+ * value scale the output).  Cache bytes per token halve, which is what bounds this kernel.
+ *
+ *   q                 [N_cap, H_q, D] bf16 (p->dtype must be FSR_BF16)
+ *   k_cache, v_cache  [n_pages, H_kv, P, D] or [n_pages, P, H_kv, D] (kv_layout) uint8, 16-byte aligned
+ *   k_scale, v_scale  [H_kv] float32, device
+ *   everything else as for fsr_verify_attention (same workspace size; no spec_lens argument).
+ * Needs D = 128, P = 16, H_q / H_kv <= 16, B <= 4096: FSR_EUNSUP otherwise.  Slots past a request's
+ * last token may hold any bytes, NaN codes included.
+ */
+int fsr_verify_attention_kv8(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                             const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
+                             const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p /*host*/,
+                             void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Cache append (Sec. 2.1 / Sec. 3.1: the drafted tokens of a request enter the target model as
  * new positions behind its cached context).  Row j of request i (row cu_q[i] + j of k_new /
  * v_new) is the token at logical position ctx_lens[i] + j: its key and value vectors are copied,

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     survivor_mask,
     topk_rank_check,
     verify_attention,
+    verify_attention_kv8,
     version,
 )
 from .frontier import verify_chunked  # noqa: F401
@@ -30,5 +31,5 @@ from .frontier import verify_chunked  # noqa: F401
 __all__ = [
     "FsrError", "accept_workspace_bytes", "attn_workspace_bytes", "frontier_commit", "frontier_init",
     "frontier_plan", "kv_append", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
-    "spec_accept", "survivor_mask", "topk_rank_check", "verify_attention", "verify_chunked", "version",
+    "spec_accept", "survivor_mask", "topk_rank_check", "verify_attention", "verify_attention_kv8", "verify_chunked", "version",
 ]

@@ -21,7 +21,7 @@ PROBS, LOGITS, GREEDY = 0, 1, 2
 KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
 
 SYMBOLS = [
-    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_kv_append",
+    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
@@ -162,6 +162,35 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
         _ptr(spec_lens, torch.int32, "spec_lens"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"),
         _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _ptr(workspace, name="workspace"),
         ctypes.c_size_t(ws_bytes), _stream()))
+    return out, lse
+
+
+def verify_attention_kv8(q, k_cache, v_cache, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, scale, out=None, lse=None,
+                         out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR):
+    """fsr_verify_attention_kv8: caches are uint8 tensors of E4M3 bytes, k_scale / v_scale [H_kv] float32."""
+    lib = load_library()
+    B = ctx_lens.shape[0]
+    out_dtype = out_dtype or (out.dtype if out is not None else q.dtype)
+    p = _attn_params(q, k_cache, block_tables, B, out_dtype, scale, max_q_len, max_workgroups, kv_layout)
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype, device=q.device)
+    if v_cache.shape != k_cache.shape or k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise ValueError("caches must be uint8 tensors of one shape")
+    if k_scale.shape[0] != p.H_kv or v_scale.shape[0] != p.H_kv:
+        raise ValueError("k_scale and v_scale need one entry per KV head")
+    if cu_q.shape[0] != B + 1 or block_tables.shape[0] != B:
+        raise ValueError("cu_q must have B+1 entries and block_tables B rows")
+    need = ctypes.c_size_t(0)
+    _check(lib.fsr_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(need)))
+    if workspace is None and need.value:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.fsr_verify_attention_kv8(
+        _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+        _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),
+        _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+        _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"), _ptr(lse, torch.float32, "lse"), ctypes.byref(p),
+        _ptr(workspace, name="workspace"), ctypes.c_size_t(ws_bytes), _stream()))
     return out, lse
 
 

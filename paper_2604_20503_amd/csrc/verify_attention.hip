@@ -90,6 +90,8 @@ struct FastArgs {
     int m_cap;       // rows (G * q_len) a partial slot holds = 16 * MTMAX
     int out_bf16;
     float scale_log2;
+    const float* k_scale;  // 8-bit caches: per KV head, cached key = decode(byte) * k_scale[head]; else unused
+    const float* v_scale;  // the same for values
     int cost_base;   // fixed part of a tile's cost (see tile_cost)
     int seg_tiles;   // phantom tiles in front of every item on the cost line (see the schedule)
 #ifdef FSR_TIMING
@@ -221,6 +223,36 @@ struct KVTile {
     bf16x8 k[2][4];
     s16x8 v[8];
 };
+// The same tile of an 8-bit cache: a key row is 128 bytes.  k[page][c]: key li of the page, the 16
+// bytes d = 64 c + 16 lg .. +15; v[r]: key 8 r + lane / 8 of the tile, the 16 bytes d = 16 (lane % 8) .. +15.
+struct KVTile8 {
+    u32x4 k[2][2];
+    u32x4 v[4];
+};
+template <bool KV8> struct TileOf { typedef KVTile type; };
+template <> struct TileOf<true> { typedef KVTile8 type; };
+typedef const __attribute__((address_space(1))) u32x4 gmem_u32x4;
+
+// 4 E4M3 bytes -> 4 bf16 (exact: 3 mantissa bits fit bf16's 7), as two packed pairs.
+__device__ __forceinline__ void e4m3x4_to_bf16(uint32_t w, uint32_t& lo, uint32_t& hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    // (elements to scalars before the bit casts: a bit cast of a vector-element expression was seen to read element 0)
+    const float a0 = a[0], a1 = a[1], b0 = b[0], b1 = b[1];
+    lo = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, a1), __builtin_bit_cast(uint32_t, a0), 0x07060302u);
+    hi = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b1), __builtin_bit_cast(uint32_t, b0), 0x07060302u);
+}
+// 16 E4M3 bytes -> 16 bf16 in two registers-of-8
+__device__ __forceinline__ void e4m3x16_to_bf16(u32x4 w, u32x4& first8, u32x4& next8) {
+    const uint32_t w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
+    uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
+    e4m3x4_to_bf16(w0, a0, a1);
+    e4m3x4_to_bf16(w1, a2, a3);
+    e4m3x4_to_bf16(w2, b0, b1);
+    e4m3x4_to_bf16(w3, b2, b3);
+    first8 = u32x4{a0, a1, a2, a3};
+    next8 = u32x4{b0, b1, b2, b3};
+}
 
 // What a workgroup processes between two merges: tiles [tile_a, tile_e) of item (i, kvh) for the
 // query rows j0 .. j0 + rows_g - 1 of the request.  final_out: the tiles are the whole item, so
@@ -270,19 +302,20 @@ __device__ __forceinline__ const const_i32* uniform(const const_i32* p) {
 // apart, heads 4 KB apart).  TM = true: a page holds one [H_kv, D] block per token (keys of a head
 // H_kv * 256 bytes apart, heads 256 bytes apart).  A template parameter, so that the first layout
 // keeps every offset as an instruction immediate.
-template <bool TM>
-__device__ __forceinline__ int key_stride(const FastArgs& a) { return TM ? a.H_kv * kD * 2 : kD * 2; }
-template <bool TM>
-__device__ __forceinline__ int head_stride() { return TM ? kD * 2 : kP * kD * 2; }
+// KV8 = true: the caches hold one byte per element (OCP E4M3, see stage_and_scores) instead of bf16.
+template <bool TM, bool KV8>
+__device__ __forceinline__ int key_stride(const FastArgs& a) { return (TM ? a.H_kv * kD : kD) * (KV8 ? 1 : 2); }
+template <bool TM, bool KV8>
+__device__ __forceinline__ int head_stride() { return (TM ? kD : kP * kD) * (KV8 ? 1 : 2); }
 
-template <bool TM>
+template <bool TM, bool KV8>
 __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment& sg) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     KVStream st;
     st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
-    st.k_head = (gmem_char*)a.k + (size_t)kvh * head_stride<TM>();
-    st.v_head = (gmem_char*)a.v + (size_t)kvh * head_stride<TM>();
+    st.k_head = (gmem_char*)a.k + (size_t)kvh * head_stride<TM, KV8>();
+    st.v_head = (gmem_char*)a.v + (size_t)kvh * head_stride<TM, KV8>();
     const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
     st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
     const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
@@ -358,8 +391,8 @@ struct ShareWalker {
     }
 };
 
-template <bool TM>
-__device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, KVTile& t, int ti) {
+template <bool TM, bool KV8>
+__device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, typename TileOf<KV8>::type& t, int ti) {
     const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
     KVStream st;
     st.bt = uniform(sv.bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
@@ -367,12 +400,10 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     ti = uniform(ti);
     const bool real = ti < st.nw;
     const int kb = st.kb0 + min(ti, st.nw - 1) * kStep;
-    // per-lane byte offsets inside a 4 KB (page, head) block: every load is then
+    // per-lane byte offsets inside a (page, head) block: every load is then
     // "uniform base + this offset + immediate", with no per-load address arithmetic
-    const int ks = key_stride<TM>(a);
-    const int kl = real ? li * ks + lg * 16 : 0;  // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
-    const int vl = real ? lg * ks + li * 16 : 0;  // V: key lg (+ 4 r), 16-byte chunk li
-    const size_t page_bytes = (size_t)a.H_kv * kP * kD * 2;
+    const int ks = key_stride<TM, KV8>(a);
+    const size_t page_bytes = (size_t)a.H_kv * kP * kD * (KV8 ? 1 : 2);
     // the second page exists only if the request has tokens there
     int pg0 = st.bt[kb >> 4];
     int pg1 = (kb + kP < st.kv_total) ? st.bt[(kb >> 4) + 1] : pg0;
@@ -382,21 +413,37 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     gmem_char* kp1 = st.k_head + (size_t)pg1 * page_bytes;
     gmem_char* vp0 = st.v_head + (size_t)pg0 * page_bytes;
     gmem_char* vp1 = st.v_head + (size_t)pg1 * page_bytes;
+    if constexpr (KV8) {
+        const int kl = real ? li * ks + lg * 16 : 0;                  // K: key li, bytes 16 lg (+ 64 c)
+        const int vl = real ? (lane >> 3) * ks + (lane & 7) * 16 : 0;  // V: key lane / 8 (+ 8 per r), chunk lane % 8
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        t.k[0][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp0 + kl + 64 * kk));
-        t.k[1][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp1 + kl + 64 * kk));
-    }
-    // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
+        for (int c = 0; c < 2; ++c) {
+            t.k[0][c] = *(gmem_u32x4*)(kp0 + kl + 64 * c);
+            t.k[1][c] = *(gmem_u32x4*)(kp1 + kl + 64 * c);
+        }
+        t.v[0] = *(gmem_u32x4*)(vp0 + vl);
+        t.v[1] = *(gmem_u32x4*)(vp0 + vl + 8 * ks);
+        t.v[2] = *(gmem_u32x4*)(vp1 + vl);
+        t.v[3] = *(gmem_u32x4*)(vp1 + vl + 8 * ks);
+    } else {
+        const int kl = real ? li * ks + lg * 16 : 0;  // K: key li, 16 bytes at d = 8 lg (+ 32 kk)
+        const int vl = real ? lg * ks + li * 16 : 0;  // V: key lg (+ 4 r), 16-byte chunk li
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        t.v[r] = *(gmem_s16x8*)(vp0 + vl + 4 * ks * r);
-        t.v[4 + r] = *(gmem_s16x8*)(vp1 + vl + 4 * ks * r);
+        for (int kk = 0; kk < 4; ++kk) {
+            t.k[0][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp0 + kl + 64 * kk));
+            t.k[1][kk] = __builtin_bit_cast(bf16x8, *(gmem_s16x8*)(kp1 + kl + 64 * kk));
+        }
+        // V: lane copies 16-byte chunk li of keys 4 r + lg, r = 0..7 (r >= 4: second page)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            t.v[r] = *(gmem_s16x8*)(vp0 + vl + 4 * ks * r);
+            t.v[4 + r] = *(gmem_s16x8*)(vp1 + vl + 4 * ks * r);
+        }
     }
 }
 
 // Process one segment: stream the wave's tiles, merge the 4 waves, write the result or the partial.
-template <int MT, bool TM>
+template <int MT, bool TM, bool KV8>
 __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem, int seg_no) {
     FSR_STAMP(seg_no * 5 + 2);
     // everything that is the same for the whole wave goes to scalar registers
@@ -424,13 +471,21 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
 #pragma unroll
         for (int db = 0; db < 8; ++db) vr_off[db] = vtile_off(r0, 2 * db + ((li & 3) >> 1)) + (li & 1) * 8;
     }
-    auto issue = [&](KVTile& t, int ti) { issue_tile<TM>(a, st, t, ti); };
+    typedef typename TileOf<KV8>::type Tile;
+    auto issue = [&](Tile& t, int ti) { issue_tile<TM, KV8>(a, st, t, ti); };
+    // with 8-bit caches the per-head key scale joins the softmax scale and the value scale the merge
+    const float sl2 = KV8 ? a.scale_log2 * a.k_scale[kvh] : a.scale_log2;
+    const float v_mul = KV8 ? a.v_scale[kvh] : 1.0f;
+    // LDS store offsets of the 8-bit V path: key 8 r + lane / 8, the two bf16 chunks of its 16 bytes
+    int v8_off[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v8_off[r] = KV8 ? vtile_off(8 * r + (lane >> 3), 2 * (lane & 7)) : 0;
     // The K/V stream does not depend on Q: start it before anything else of the segment.
     // Two tiles in flight per wave.  (A third, where the registers would allow it, does not raise
     // the rate: a compute unit draws only about twice its even share of the HBM bandwidth however
     // much it keeps in flight.)
     constexpr int kDepth = 2;
-    KVTile ta, tb;
+    Tile ta, tb;
     if (nw > 0) {
         issue(ta, 0);
         issue(tb, 1);
@@ -451,7 +506,10 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         const int m = mt * 16 + li;
         const bool ok = m < M_g;
         const int j = j0 + m / G, gq = m % G;
-        const uint16_t* qp = a.q + ((size_t)(q0 + (ok ? j : j0)) * a.H_q + kvh * G + (ok ? gq : 0)) * kD + 8 * lg + 32 * kk;
+        // the contraction index of matrix instruction kk, lane group lg covers d = 32 kk + 8 lg .. +7 with bf16
+        // caches; with 8-bit ones a lane's 16-byte K chunk holds d = 64 c + 16 lg .. +15, split over kk = 2c, 2c+1
+        const int d_off = KV8 ? 64 * (kk >> 1) + 16 * lg + 8 * (kk & 1) : 8 * lg + 32 * kk;
+        const uint16_t* qp = a.q + ((size_t)(q0 + (ok ? j : j0)) * a.H_q + kvh * G + (ok ? gq : 0)) * kD + d_off;
         s16x8 t = *reinterpret_cast<const s16x8*>(qp);
         if (!ok) t = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
         *reinterpret_cast<s16x8*>(qbuf + (pr * 64 + lane) * 16) = t;
@@ -475,15 +533,45 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     // ---- phase 1 of a tile: V to LDS, S^T = K Q^T on the matrix cores; afterwards the tile's
     // registers are free for the next loads.
     // s[mt][kt][e] = score(key kb + 16 kt + 4 lg + e, query mt*16 + li)
-    auto stage_and_scores = [&](KVTile& t, int kb, f32x4 (&s)[MT][2]) {
-        if (kb + kTile > kv_total) {  // slots past the request's last token may hold anything: zero them
+    auto stage_and_scores = [&](Tile& t, int kb, f32x4 (&s)[MT][2]) {
+        bf16x8 kop[2][4];  // K as matrix operands
+        if constexpr (KV8) {
+            // bytes -> bf16 in registers (exact), then everything is as with a bf16 cache
+            if (kb + kTile > kv_total) {  // slots past the request's last token may hold anything: zero them
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (kb + 8 * r + (lane >> 3) >= kv_total) t.v[r] = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u32x4 lo8, hi8;
+                e4m3x16_to_bf16(t.v[r], lo8, hi8);
+                *reinterpret_cast<u32x4*>(vbuf + v8_off[r]) = lo8;
+                *reinterpret_cast<u32x4*>(vbuf + v8_off[r] + 16) = hi8;
+            }
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    u32x4 lo8, hi8;
+                    e4m3x16_to_bf16(t.k[pg][c], lo8, hi8);
+                    kop[pg][2 * c] = __builtin_bit_cast(bf16x8, lo8);
+                    kop[pg][2 * c + 1] = __builtin_bit_cast(bf16x8, hi8);
+                }
+        } else {
+            if (kb + kTile > kv_total) {  // slots past the request's last token may hold anything: zero them
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (kb + 4 * r + lg >= kv_total) t.v[r] = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
 #pragma unroll
             for (int r = 0; r < 8; ++r)
-                if (kb + 4 * r + lg >= kv_total) t.v[r] = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
+                *reinterpret_cast<s16x8*>(vbuf + ((r & 1) ? vw_odd : vw_even) + 1024 * r) = t.v[r];
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-            *reinterpret_cast<s16x8*>(vbuf + ((r & 1) ? vw_odd : vw_even) + 1024 * r) = t.v[r];
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) kop[pg][kk] = t.k[pg][kk];
+        }
         // all Q^T operands first (one batch of LDS reads in flight), then the matrix instructions
         bf16x8 qop[MT][4];
 #pragma unroll
@@ -496,8 +584,8 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             s[mt][0] = s[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                s[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][kk], qop[mt][kk], s[mt][0], 0, 0, 0);
-                s[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][kk], qop[mt][kk], s[mt][1], 0, 0, 0);
+                s[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][kk], qop[mt][kk], s[mt][0], 0, 0, 0);
+                s[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][kk], qop[mt][kk], s[mt][1], 0, 0, 0);
             }
         }
         __builtin_amdgcn_sched_group_barrier(0x200, 8, 0);       // V stores
@@ -550,7 +638,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         bf16x8 pl;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            const float p0 = fast_exp2(fmaf(x[e], a.scale_log2, neg_m)), p1 = fast_exp2(fmaf(x[e + 1], a.scale_log2, neg_m));
+            const float p0 = fast_exp2(fmaf(x[e], sl2, neg_m)), p1 = fast_exp2(fmaf(x[e + 1], sl2, neg_m));
             psum += p0 + p1;
             const uint32_t b0 = __builtin_bit_cast(uint32_t, p0), b1 = __builtin_bit_cast(uint32_t, p1);
             hi_pk[e >> 1] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
@@ -589,7 +677,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         bool any = false;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            lane_max[mt] = a.scale_log2 * max8(x[mt]);
+            lane_max[mt] = sl2 * max8(x[mt]);
             any |= lane_max[mt] > m_run[mt] + kFastSlack;
         }
         if (__builtin_amdgcn_ballot_w64(any) != 0) {  // first keys of a row, or trouble
@@ -612,7 +700,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         f32x4 s[MT][2];
         // one tile: wait for it, stage V, scores; refill its registers with the tile kDepth
         // further on (past the end: a harmless repeat of the last tile); softmax and P V
-        auto fast_tile = [&](KVTile& tl, int t) {
+        auto fast_tile = [&](Tile& tl, int t) {
             const bool real = t < nw;
             if (real) stage_and_scores(tl, kb0 + t * kStep, s);
             __builtin_amdgcn_sched_barrier(0);
@@ -636,7 +724,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     if (redo) {
         constexpr float kSlack = 8.0f;
         reset_state();
-        auto issue_one = [&](KVTile& t, int ti) {
+        auto issue_one = [&](Tile& t, int ti) {
             if (ti < nw) issue(t, ti);
         };
         auto needs_raise = [&](int kb, const f32x4 (&s)[MT][2]) {
@@ -644,7 +732,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             float x[MT][8];
             masked_scores(kb, s, x);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) any |= a.scale_log2 * max8(x[mt]) > m_run[mt] + kSlack;
+            for (int mt = 0; mt < MT; ++mt) any |= sl2 * max8(x[mt]) > m_run[mt] + kSlack;
             return __builtin_amdgcn_ballot_w64(any) != 0;
         };
         auto raise_refs = [&](int kb, const f32x4 (&s)[MT][2]) {
@@ -652,7 +740,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             masked_scores(kb, s, x);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const float lane_max = a.scale_log2 * max8(x[mt]);
+                const float lane_max = sl2 * max8(x[mt]);
                 float row_max = fmaxf(lane_max, __shfl_xor(lane_max, 16, 64));
                 row_max = fmaxf(row_max, __shfl_xor(row_max, 32, 64));
                 const float m_new = row_max > m_run[mt] + kSlack ? row_max : m_run[mt];
@@ -720,7 +808,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww) m_star = fmaxf(m_star, red_m[ww * 16 * kMaxMT + mt * 16 + li]);
         const float m_use = m_star == -INFINITY ? 0.0f : m_star;
-        const float f = fast_exp2(m_run[mt] - m_use);
+        const float f = fast_exp2(m_run[mt] - m_use) * v_mul;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
             const f32x4 o = acc[mt][db] * f;
@@ -783,11 +871,11 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
 }
 
-template <int MTMAX, bool TM>
+template <int MTMAX, bool TM, bool KV8>
 __device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem,
                                                 int seg_no) {
     const int mt = (a.G * sg.rows_g + 15) >> 4;
-#define FSR_SEG(MT) attend_segment<MT, TM>(a, sg, st, smem, seg_no)
+#define FSR_SEG(MT) attend_segment<MT, TM, KV8>(a, sg, st, smem, seg_no)
     if constexpr (MTMAX == 1) {
         FSR_SEG(1);
     } else if constexpr (MTMAX == 2) {
@@ -894,7 +982,7 @@ __device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned 
 // inside one share is finished by that workgroup; an item cut by share boundaries leaves one
 // partial per piece, and the workgroup whose piece arrives last combines them (no workgroup ever
 // waits for another).
-template <int MTMAX, bool TM>
+template <int MTMAX, bool TM, bool KV8>
 __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
@@ -923,8 +1011,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     Segment cur;
     int seg_no = 0;
     while (wk.next(a, cur)) {
-        const KVStream st = make_stream<TM>(a, cur);
-        attend_dispatch<MTMAX, TM>(a, cur, st, smem, min(seg_no, 2));
+        const KVStream st = make_stream<TM, KV8>(a, cur);
+        attend_dispatch<MTMAX, TM, KV8>(a, cur, st, smem, min(seg_no, 2));
         ++seg_no;
         if (wk.cut) {
             // pieces of this item: the workgroups that own its first .. last tile; workgroup bb owns
@@ -1126,18 +1214,21 @@ extern "C" int fsr_attn_workspace_bytes(const fsr_attn_params* p, size_t* out_by
     return FSR_OK;
 }
 
-extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache,
-                                    const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* spec_lens,
-                                    const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
-                                    void* workspace, size_t ws_bytes, void* stream) {
-    (void)spec_lens;
+namespace {
+// Both entry points: kv8 = the caches hold E4M3 bytes with per-head scales (fast path only).
+int attention_call(const void* q, const void* k_cache, const void* v_cache, const float* k_scale, const float* v_scale, bool kv8,
+                   const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q, void* out, float* lse,
+                   const fsr_attn_params* p, void* workspace, size_t ws_bytes, void* stream) {
     int rc = validate(p, "fsr_verify_attention");
     if (rc != FSR_OK) return rc;
     if (p->B == 0 || p->N_cap == 0) return FSR_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !ctx_lens || !cu_q || !out)
         return fail(FSR_EINVAL, "fsr_verify_attention: null pointer among q/k_cache/v_cache/block_tables/ctx_lens/cu_q/out");
+    if (kv8 && (!k_scale || !v_scale)) return fail(FSR_EINVAL, "fsr_verify_attention_kv8: k_scale / v_scale is null");
     hipStream_t s = (hipStream_t)stream;
     const Plan pl = make_plan(*p);
+    if (kv8 && !pl.fast)
+        return fail(FSR_EUNSUP, "fsr_verify_attention_kv8: 8-bit caches need bf16 queries, D = 128, P = 16, H_q / H_kv <= 16, B <= %d", kMaxB);
     if (pl.fast) {
         const size_t need = pl.bytes_o + pl.bytes_ml + pl.bytes_cnt;
         if (!workspace || ws_bytes < need) return fail(FSR_EWS, "fsr_verify_attention: workspace %zu bytes, need %zu", ws_bytes, need);
@@ -1156,6 +1247,7 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
         a.max_pages = p->max_pages; a.n_pages = p->n_pages;
         a.nb = pl.nb; a.m_cap = 16 * pl.mt_max; a.out_bf16 = p->out_dtype == FSR_BF16;
         a.scale_log2 = p->scale * kLog2e;
+        a.k_scale = k_scale; a.v_scale = v_scale;
         a.seg_tiles = kSegTiles;
         a.cost_base = kCostBase;
 #ifdef FSR_TIMING
@@ -1163,10 +1255,14 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
 #endif
         const dim3 grid(pl.nb), block(kThreads);
 #define FSR_LAUNCH(MT)                                                                              \
-    if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                         \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, true>), grid, block, kFastSmem, s, a);           \
+    if (kv8 && p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                  \
+        hipLaunchKernelGGL((attn_stream_kernel<MT, true, true>), grid, block, kFastSmem, s, a);     \
+    else if (kv8)                                                                                   \
+        hipLaunchKernelGGL((attn_stream_kernel<MT, false, true>), grid, block, kFastSmem, s, a);    \
+    else if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                    \
+        hipLaunchKernelGGL((attn_stream_kernel<MT, true, false>), grid, block, kFastSmem, s, a);    \
     else                                                                                            \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, false>), grid, block, kFastSmem, s, a)
+        hipLaunchKernelGGL((attn_stream_kernel<MT, false, false>), grid, block, kFastSmem, s, a)
         switch (pl.mt_max) {
             case 1: FSR_LAUNCH(1); break;
             case 2: FSR_LAUNCH(2); break;
@@ -1194,4 +1290,22 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
         else hipLaunchKernelGGL((attn_generic_kernel<uint16_t, float, 128>), grid, block, 0, s, g);
     }
     return check_launch("attn_generic_kernel");
+}
+}  // namespace
+
+extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache,
+                                    const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* spec_lens,
+                                    const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
+                                    void* workspace, size_t ws_bytes, void* stream) {
+    (void)spec_lens;
+    return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, workspace,
+                          ws_bytes, stream);
+}
+
+extern "C" int fsr_verify_attention_kv8(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                                        const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
+                                        const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
+                                        void* workspace, size_t ws_bytes, void* stream) {
+    return attention_call(q, k_cache, v_cache, k_scale, v_scale, true, block_tables, ctx_lens, cu_q, out, lse, p, workspace,
+                          ws_bytes, stream);
 }

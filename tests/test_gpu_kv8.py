@@ -1,0 +1,122 @@
+"""GPU parity: verification attention over 8-bit (E4M3) KV caches vs the oracle reading the same bytes.
+The bytes widen exactly, so the bound is the bf16-cache kernel's: 2e-3 relative on the fp32 output (measured
+~1e-5), a bf16 output within its rounding on top."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_utils import announce, check_attention, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fsr():
+    import paper_2604_20503_amd as f
+    f.load_library()
+    return f
+
+
+def quantise(b, seed, poison=False):
+    """The batch's bf16 caches re-stored as E4M3 bytes with per-head scales; unused slots optionally NaN codes."""
+    rng = np.random.default_rng(seed)
+    k_scale = rng.uniform(0.01, 0.05, b.H_kv).astype(np.float32)
+    v_scale = rng.uniform(0.01, 0.05, b.H_kv).astype(np.float32)
+    kf, vf = workloads.bf16_bits_to_f32(b.k_cache), workloads.bf16_bits_to_f32(b.v_cache)
+    k8 = workloads.f32_to_e4m3_bits(kf / k_scale.reshape(1, -1, 1, 1))
+    v8 = workloads.f32_to_e4m3_bits(vf / v_scale.reshape(1, -1, 1, 1))
+    if poison:
+        used = np.zeros((b.n_pages, b.P), bool)
+        for i in range(b.B):
+            for t in range(int(b.ctx_lens[i] + b.spec_lens[i] + 1)):
+                used[b.block_tables[i, t // b.P], t % b.P] = True
+        for c in (k8, v8):
+            m = np.moveaxis(c, 1, 2)      # view [page, slot, head, d]
+            m[~used] = 0x7F               # NaN code
+    return k8, v8, k_scale, v_scale
+
+
+def run_pair(fsr, oracle, b, k8, v8, k_scale, v_scale, out_dtype, token_major=False, max_q_len=None):
+    o_ref, lse_ref = oracle.verify_attention_kv8(b.q, k8, v8, k_scale, v_scale, b.block_tables, b.ctx_lens, b.cu_q,
+                                                 H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, scale=b.scale)
+    kd, vd = (np.ascontiguousarray(np.swapaxes(c, 1, 2)) if token_major else c for c in (k8, v8))
+    lse = torch.empty(b.N, b.H_q, dtype=torch.float32, device="cuda")
+    out, _ = fsr.verify_attention_kv8(dev(b.q, True), dev(kd), dev(vd), dev(k_scale), dev(v_scale), dev(b.block_tables),
+                                      dev(b.ctx_lens), dev(b.cu_q), scale=b.scale, out_dtype=out_dtype, lse=lse,
+                                      max_q_len=b.S_max + 1 if max_q_len is None else max_q_len,
+                                      kv_layout=fsr.binding.KV_TOKEN_MAJOR if token_major else fsr.binding.KV_HEAD_MAJOR)
+    torch.cuda.synchronize()
+    err = check_attention(out, o_ref, "bf16", b.N)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
+    return err
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("heads", [(32, 8), (8, 8), (64, 8), (16, 1)])
+def test_kv8_small(fsr, oracle, heads, out_dtype):
+    H_q, H_kv = heads
+    announce(f"attention kv8 small heads={heads} out={out_dtype}")
+    ctx = [0, 1, 15, 16, 31, 33, 100, 257, 511, 640, 700, 1029]
+    spec = [3, 0, 8, 1, 2, 7, 4, 10, 5, 6, 0, 9]
+    b = workloads.make_batch(2, rep=H_q + 1, with_probs=False, H_q=H_q, H_kv=H_kv, ctx_lens=ctx, spec_lens=spec)
+    err = run_pair(fsr, oracle, b, *quantise(b, H_q), out_dtype)
+    print(f"kv8 heads={heads} out={out_dtype} max rel err {err:.3e}")
+
+
+def test_kv8_token_major_and_nan_codes_beyond_length(fsr, oracle):
+    announce("attention kv8 token-major + NaN codes beyond length")
+    b = workloads.make_batch(2, rep=9, with_probs=False, ctx_lens=[37, 200, 16, 95, 1500], spec_lens=[2, 5, 0, 7, 8])
+    q = quantise(b, 1, poison=True)
+    run_pair(fsr, oracle, b, *q, torch.float32, token_major=False)
+    run_pair(fsr, oracle, b, *q, torch.float32, token_major=True)
+
+
+def test_kv8_every_code_decodes_as_the_format_says(fsr, oracle):
+    """A one-row request whose single key is constant and whose value row runs through every byte code: the
+    output is the decoded values themselves (softmax over one key), so each finite code is checked on its own."""
+    announce("attention kv8 all codes")
+    b = workloads.make_batch(2, rep=11, with_probs=False, H_q=8, H_kv=8, ctx_lens=[0, 0], spec_lens=[0, 0])
+    k8 = np.full(b.k_cache.shape, 0x38, np.uint8)   # 1.0
+    v8 = np.zeros(b.v_cache.shape, np.uint8)
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F], np.uint8)   # 254 finite codes
+    for i in range(2):
+        page = b.block_tables[i, 0]
+        for h in range(8):
+            v8[page, h, 0, :] = codes[(np.arange(128) + 128 * i + 17 * h) % len(codes)]
+    ones = np.ones(8, np.float32)
+    o_ref, _ = oracle.verify_attention_kv8(b.q, k8, v8, ones, ones, b.block_tables, b.ctx_lens, b.cu_q,
+                                           H_q=8, H_kv=8, D=b.D, P=b.P, scale=b.scale)
+    out, _ = fsr.verify_attention_kv8(dev(b.q, True), dev(k8), dev(v8), dev(ones), dev(ones), dev(b.block_tables),
+                                      dev(b.ctx_lens), dev(b.cu_q), scale=b.scale, out_dtype=torch.float32, max_q_len=1)
+    torch.cuda.synchronize()
+    # (the row's own probability is exp2 of a rounding residue, not exactly 1: a few ulp, far below the 6 % between codes)
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), o_ref, rtol=1e-6, atol=0)
+
+
+def test_kv8_config2_sampled_rows(fsr, oracle):
+    """Workload 2's shape with 8-bit caches, in the launch configuration of the bench; checked on 3 requests."""
+    announce("attention kv8 config2")
+    b = workloads.make_batch(2, with_probs=False)
+    k8, v8, ks, vs = quantise(b, 2)
+    out, _ = fsr.verify_attention_kv8(dev(b.q, True), dev(k8), dev(v8), dev(ks), dev(vs), dev(b.block_tables), dev(b.ctx_lens),
+                                      dev(b.cu_q), scale=b.scale, out_dtype=torch.float32, max_q_len=b.S_max + 1)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    for i in (0, 7, 15):
+        r0, r1 = int(b.cu_q[i]), int(b.cu_q[i + 1])
+        o_ref, _ = oracle.verify_attention_kv8(b.q[r0:r1], k8, v8, ks, vs, b.block_tables[i:i + 1], b.ctx_lens[i:i + 1],
+                                               np.array([0, r1 - r0], np.int32), H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, scale=b.scale)
+        check_attention(torch.from_numpy(out[r0:r1]), o_ref, "bf16", r1 - r0)
+
+
+def test_kv8_unsupported_shapes_are_refused(fsr):
+    announce("attention kv8 refusals")
+    q = torch.zeros(4, 8, 64, dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros(2, 8, 16, 64, dtype=torch.uint8, device="cuda")
+    sc = torch.ones(8, device="cuda")
+    bt = torch.zeros(1, 2, dtype=torch.int32, device="cuda")
+    with pytest.raises(fsr.FsrError) as e:
+        fsr.verify_attention_kv8(q, kc, kc, sc, sc, bt, torch.zeros(1, dtype=torch.int32, device="cuda"),
+                                 torch.tensor([0, 4], dtype=torch.int32, device="cuda"), scale=1.0)
+    assert e.value.code == -3
