@@ -93,6 +93,28 @@ def decode_e4m3(codes):
     return out
 
 
+def encode_e4m3(x):
+    """E4M3 bytes of fp32 values: nearest, ties to the even code, saturating at 448."""
+    lib = _load()
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    lib.fo_encode_e4m3(_p(x), _p(out), ctypes.c_int64(x.size))
+    return out
+
+
+def kv_append_kv8(k_new_bits, v_new_bits, k_cache8, v_cache8, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, P,
+                  token_major=False):
+    """Cache append into 8-bit caches: a bf16 key element x of KV head g is stored as the E4M3 byte of
+    fl32(x / k_scale[g]) (one fp32 division, then one rounding to 8 bits), values likewise; then the bytes go
+    where fo_kv_append puts them.  Returns the updated (k_cache8, v_cache8)."""
+    def quantise(bits, scale):
+        x = (_c(bits, np.uint16).astype(np.uint32) << 16).view(np.float32)
+        y = (x / np.asarray(scale, dtype=np.float32).reshape(1, -1, 1)).astype(np.float32)
+        return encode_e4m3(y)
+    return kv_append(quantise(k_new_bits, k_scale), quantise(v_new_bits, v_scale), k_cache8, v_cache8, block_tables,
+                     ctx_lens, cu_q, P=P, token_major=token_major)
+
+
 def verify_attention_kv8(q_bits, k_cache8, v_cache8, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, H_q, H_kv, D, P,
                          scale, token_major=False):
     """The same attention with the caches stored as E4M3 bytes: cached key = decode(byte) * k_scale[kv head],

@@ -88,6 +88,35 @@ void fo_decode_e4m3(const uint8_t *codes, double *out, int64_t n)
 }
 
 /*
+ * The E4M3 byte that stands for x: the finite code whose value is nearest to x, the one with an
+ * even code on a tie (round to nearest even), magnitudes beyond the largest finite value (448)
+ * giving that value (saturation), NaN giving the NaN code.  Written as a search over the 127
+ * non-negative finite codes so that it is the definition and nothing else.
+ */
+void fo_encode_e4m3(const float *x, uint8_t *out, int64_t n)
+{
+    double value[127];
+    for (int c = 0; c < 127; ++c) {
+        const uint8_t code = (uint8_t)c;
+        fo_decode_e4m3(&code, &value[c], 1);
+    }
+    for (int64_t k = 0; k < n; ++k) {
+        if (isnan(x[k])) {
+            out[k] = 0x7f;
+            continue;
+        }
+        const double mag = fabs((double)x[k]);
+        int best = 0;
+        for (int c = 1; c < 127; ++c) {
+            const double d = fabs(value[c] - mag), db = fabs(value[best] - mag);
+            if (d < db || (d == db && (c & 1) == 0))
+                best = c;
+        }
+        out[k] = (uint8_t)(best | (signbit(x[k]) ? 0x80 : 0));
+    }
+}
+
+/*
  * Attention of every query row over its request's cached keys/values.
  *
  * Request i owns rows cu_q[i] .. cu_q[i+1]-1.  Row j of request i is the query of the

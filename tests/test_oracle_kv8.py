@@ -61,3 +61,41 @@ def test_kv8_attention_equals_ordinary_attention_on_decoded_caches():
                                           H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, scale=b.scale)
     assert np.allclose(out3, 2 * out2, rtol=1e-14, atol=0)
     assert np.isfinite(out).all() and out.shape == (b.N, b.H_q, b.D)
+
+
+def test_oracle_encoder_against_torch_and_the_generators_encoder():
+    """The oracle's own E4M3 encoder (a search over the codes) against torch's conversion and against the
+    input generator's table-based encoder: three independent writings of the same rounding."""
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(5000) * 4, rng.standard_normal(2000) * 2e-2, rng.uniform(-448, 448, 1000),
+                        [0.0, -0.0, 448.0, -448.0, 2.0 ** -10, 3 * 2.0 ** -10, 5 * 2.0 ** -10, 2.0 ** -9, 0.9375, 1.0625,
+                         17.0, 19.0, 460.0, -1e6]]).astype(np.float32)
+    got = oracle.encode_e4m3(x)
+    inside = np.abs(x) <= 448
+    ref = torch.from_numpy(x[inside]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(got[inside], ref)
+    assert np.array_equal(got, workloads.f32_to_e4m3_bits(x))          # saturation included
+    assert oracle.encode_e4m3(np.float32([np.nan]))[0] == 0x7F
+    # every finite code is a fixed point
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F], np.uint8)
+    assert np.array_equal(oracle.encode_e4m3(oracle.decode_e4m3(codes).astype(np.float32)), codes)
+
+
+def test_quantising_append_is_quantise_then_append():
+    b = workloads.make_batch(2, rep=4, with_probs=False, ctx_lens=[5, 17, 30], spec_lens=[2, 0, 3])
+    rng = np.random.default_rng(2)
+    ks, vs = rng.uniform(0.01, 0.1, b.H_kv).astype(np.float32), rng.uniform(0.01, 0.1, b.H_kv).astype(np.float32)
+    k_new = workloads.f32_to_bf16_bits(rng.standard_normal((b.N, b.H_kv, b.D)).astype(np.float32))
+    v_new = workloads.f32_to_bf16_bits(rng.standard_normal((b.N, b.H_kv, b.D)).astype(np.float32))
+    kc0 = rng.integers(0, 127, size=b.k_cache.shape).astype(np.uint8)
+    vc0 = rng.integers(0, 127, size=b.k_cache.shape).astype(np.uint8)
+    kc, vc = oracle.kv_append_kv8(k_new, v_new, kc0, vc0, ks, vs, b.block_tables, b.ctx_lens, b.cu_q, P=b.P)
+    changed = 0
+    for i in range(b.B):
+        for j in range(int(b.cu_q[i + 1] - b.cu_q[i])):
+            t = int(b.ctx_lens[i]) + j
+            page, slot, row = b.block_tables[i, t // b.P], t % b.P, int(b.cu_q[i]) + j
+            want = workloads.f32_to_e4m3_bits(workloads.bf16_bits_to_f32(k_new[row]) / ks[:, None])
+            assert np.array_equal(kc[page, :, slot, :], want)
+            changed += 1
+    assert changed == b.N and (kc != kc0).sum() <= b.N * b.H_kv * b.D and (kc != kc0).any()
