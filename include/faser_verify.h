@@ -150,6 +150,20 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
                          void* stream);
 
 /*
+ * Cache append (Sec. 2.1 / Sec. 3.1, as fsr_kv_append) into caches stored in 8 bits: element x of a bf16 key
+ * row of KV head g is stored as the E4M3 byte nearest to fl32(x / k_scale[g]) (ties to the even code, magnitudes
+ * beyond 448 saturate, NaN stays NaN); values likewise with v_scale.  fsr_verify_attention_kv8 reads them back as
+ * decode(byte) * scale.
+ *   k_new, v_new      [N_cap, H_kv, D] bf16 (p->dtype must be FSR_BF16), D a multiple of 16
+ *   k_cache, v_cache  uint8 caches in the layout p->kv_layout names, 16-byte aligned
+ *   k_scale, v_scale  [H_kv] float32, device
+ * Positions without a page and page ids outside the pool are skipped as in fsr_kv_append.
+ */
+int fsr_kv_append_kv8(const void* k_new, const void* v_new, void* k_cache, void* v_cache, const float* k_scale,
+                      const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
+                      const int32_t* cu_q, const fsr_attn_params* p /*host*/, void* stream);
+
+/*
  * The same attention (Sec. 2.1, Sec. 3.1) over caches stored in 8 bits: every element of k_cache /
  * v_cache is one byte in the OCP E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
  * no infinities), and the cached key (value) it stands for is decode(byte) * k_scale[kv head]

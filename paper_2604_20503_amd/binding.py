@@ -21,7 +21,7 @@ PROBS, LOGITS, GREEDY = 0, 1, 2
 KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
 
 SYMBOLS = [
-    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append",
+    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
@@ -213,6 +213,20 @@ def kv_append(k_new, v_new, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, k
                              _ptr(v_cache, name="v_cache"), _ptr(block_tables, torch.int32, "block_tables"),
                              _ptr(ctx_lens, torch.int32, "ctx_lens"), _ptr(cu_q, torch.int32, "cu_q"), ctypes.byref(p),
                              _stream()))
+
+
+def kv_append_kv8(k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, kv_layout=KV_HEAD_MAJOR):
+    """fsr_kv_append_kv8: quantise the call's bf16 key / value rows to E4M3 and store them into the uint8 caches."""
+    lib = load_library()
+    B = ctx_lens.shape[0]
+    p = _attn_params(k_new, k_cache, block_tables, B, k_new.dtype, 1.0, 0, 0, kv_layout)
+    if v_new.shape != k_new.shape or v_cache.shape != k_cache.shape or k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise ValueError("rows must share a shape; caches must be uint8 tensors of one shape")
+    _check(lib.fsr_kv_append_kv8(
+        _ptr(k_new, name="k_new"), _ptr(v_new, name="v_new"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+        _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),
+        _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+        _ptr(cu_q, torch.int32, "cu_q"), ctypes.byref(p), _stream()))
 
 
 def accept_workspace_bytes(*, B, V, S_max, mode=PROBS, temperature=1.0) -> int:

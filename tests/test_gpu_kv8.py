@@ -120,3 +120,40 @@ def test_kv8_unsupported_shapes_are_refused(fsr):
         fsr.verify_attention_kv8(q, kc, kc, sc, sc, bt, torch.zeros(1, dtype=torch.int32, device="cuda"),
                                  torch.tensor([0, 4], dtype=torch.int32, device="cuda"), scale=1.0)
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+def test_kv8_append_bytes_match_oracle_then_attention(fsr, oracle, token_major):
+    """Quantising append: every stored byte equals the oracle's (fp32 division, nearest-even E4M3, saturation,
+    NaN), over magnitudes from the subnormal range to beyond 448; then attention over the appended caches."""
+    announce(f"kv8 append token_major={token_major}")
+    b = workloads.make_batch(2, rep=21, with_probs=False, ctx_lens=[0, 5, 16, 47, 300], spec_lens=[3, 0, 8, 2, 6])
+    rng = np.random.default_rng(7)
+    k8, v8, ks, vs = quantise(b, 3)
+    mag = 10.0 ** rng.uniform(-4, 1.5, size=(b.N, b.H_kv, b.D))             # x / scale spans 2^-12 .. ~3000
+    k_new = (rng.standard_normal((b.N, b.H_kv, b.D)) * mag).astype(np.float32)
+    v_new = rng.standard_normal((b.N, b.H_kv, b.D)).astype(np.float32) * 0.05
+    k_new[0, 0, :4] = [np.nan, 1e30, -1e30, 0.0]
+    k_bits, v_bits = workloads.f32_to_bf16_bits(k_new), workloads.f32_to_bf16_bits(v_new)
+    lay = fsr.binding.KV_TOKEN_MAJOR if token_major else fsr.binding.KV_HEAD_MAJOR
+    to_lay = (lambda c: np.ascontiguousarray(np.swapaxes(c, 1, 2))) if token_major else (lambda c: c)
+    kc_ref, vc_ref = oracle.kv_append_kv8(k_bits, v_bits, to_lay(k8), to_lay(v8), ks, vs, b.block_tables, b.ctx_lens, b.cu_q,
+                                          P=b.P, token_major=token_major)
+    kc, vc = dev(to_lay(k8)), dev(to_lay(v8))
+    fsr.kv_append_kv8(dev(k_bits, True), dev(v_bits, True), kc, vc, dev(ks), dev(vs), dev(b.block_tables), dev(b.ctx_lens),
+                      dev(b.cu_q), kv_layout=lay)
+    torch.cuda.synchronize()
+    assert np.array_equal(kc.cpu().numpy(), kc_ref) and np.array_equal(vc.cpu().numpy(), vc_ref)
+    assert (kc_ref != to_lay(k8)).any()
+    # attention over what was appended (the NaN element sits in request 0's own rows: give that row a finite value first)
+    if not token_major:
+        k_bits2 = k_bits.copy(); k_bits2[0, 0, :4] = 0
+        kc2_ref, vc2_ref = oracle.kv_append_kv8(k_bits2, v_bits, k8, v8, ks, vs, b.block_tables, b.ctx_lens, b.cu_q, P=b.P)
+        kc2, vc2 = dev(k8), dev(v8)
+        fsr.kv_append_kv8(dev(k_bits2, True), dev(v_bits, True), kc2, vc2, dev(ks), dev(vs), dev(b.block_tables), dev(b.ctx_lens), dev(b.cu_q))
+        o_ref, _ = oracle.verify_attention_kv8(b.q, kc2_ref, vc2_ref, ks, vs, b.block_tables, b.ctx_lens, b.cu_q,
+                                               H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, scale=b.scale)
+        out, _ = fsr.verify_attention_kv8(dev(b.q, True), kc2, vc2, dev(ks), dev(vs), dev(b.block_tables), dev(b.ctx_lens),
+                                          dev(b.cu_q), scale=b.scale, out_dtype=torch.float32, max_q_len=b.S_max + 1)
+        torch.cuda.synchronize()
+        check_attention(out, o_ref, "bf16", b.N)
