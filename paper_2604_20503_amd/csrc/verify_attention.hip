@@ -67,8 +67,12 @@ constexpr int kPrefOff = kQOff + kQBytes;
 constexpr int kPrefBytes = (kMaxB + 1) * 8;          // weighted tile prefix (64-bit)
 constexpr int kScanOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
 constexpr int kFastSmem = kScanOff + 64;
-constexpr int kCostBase = 1;  // a tile costs kCostBase + (16-row query tiles riding on it)
-constexpr int kSegTiles = 8;  // what starting an item costs a workgroup (merge, refill), in tiles of that item
+// Measured: a tile takes 2.0 / 2.4 / 2.5 us per wave with 1 / 2 / 3 query tiles riding on it (bandwidth, not the
+// matrix work, sets the pace), and taking up an item costs a workgroup 6 to 10 us of merge, count and refill.
+// Swept on four batches of the 16-request shape and on the 128- and 512-request shapes: base 3..6 with 12..20
+// phantom tiles is a plateau, 5 to 9 % under base 1 with 8.
+constexpr int kCostBase = 4;   // a tile costs kCostBase + (16-row query tiles riding on it)
+constexpr int kSegTiles = 16;  // what starting an item costs a workgroup (merge, refill), in tiles of that item
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
