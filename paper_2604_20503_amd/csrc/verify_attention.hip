@@ -71,7 +71,12 @@ constexpr int kFastSmem = kScanOff + 64;
 // matrix work, sets the pace), and taking up an item costs a workgroup 6 to 10 us of merge, count and refill.
 // Swept on four batches of the 16-request shape and on the 128- and 512-request shapes: base 3..6 with 12..20
 // phantom tiles is a plateau, 5 to 9 % under base 1 with 8.
-constexpr int kCostBase = 4;   // a tile costs kCostBase + (16-row query tiles riding on it)
+// With many items per workgroup the per-item costs average out and time follows the bytes, i.e. the tile count:
+// the 256- and 512-request shapes keep gaining up to base 16 (another 8 % and 5 %), while the 16-request shape,
+// where a workgroup holds one or two long items whose fixed costs grow with the query tiles, is best at 4.  The
+// host therefore sets the base to twice the items per workgroup, between kCostBase and kCostBaseMax.
+constexpr int kCostBase = 4;   // a tile costs cost_base + (16-row query tiles riding on it)
+constexpr int kCostBaseMax = 16;
 constexpr int kSegTiles = 16;  // what starting an item costs a workgroup (merge, refill), in tiles of that item
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -1253,7 +1258,7 @@ int attention_call(const void* q, const void* k_cache, const void* v_cache, cons
         a.scale_log2 = p->scale * kLog2e;
         a.k_scale = k_scale; a.v_scale = v_scale;
         a.seg_tiles = kSegTiles;
-        a.cost_base = kCostBase;
+        a.cost_base = (int)std::min<long long>(kCostBaseMax, std::max<long long>(kCostBase, 2LL * p->B * p->H_kv / pl.nb));
 #ifdef FSR_TIMING
         a.dbg = (long long*)((char*)workspace + need);  // the timing build expects 1 MiB of slack after the workspace
 #endif
