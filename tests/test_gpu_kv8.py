@@ -157,3 +157,41 @@ def test_kv8_append_bytes_match_oracle_then_attention(fsr, oracle, token_major):
                                           dev(b.cu_q), scale=b.scale, out_dtype=torch.float32, max_q_len=b.S_max + 1)
         torch.cuda.synchronize()
         check_attention(out, o_ref, "bf16", b.N)
+
+
+def test_kv8_empty_requests_small_grid_and_append_without_a_page(fsr, oracle):
+    """Requests without rows cost nothing; a persistent grid cut down to a few workgroups gives the same result; an
+    append whose position has no page (beyond max_pages * P) or whose page id is outside the pool is skipped."""
+    announce("kv8 edge cases")
+    b = workloads.make_batch(2, rep=31, with_probs=False, ctx_lens=[40, 7, 300, 0, 64], spec_lens=[2, 0, 5, 1, 3])
+    k8, v8, ks, vs = quantise(b, 5)
+    # requests 1 and 3 get no rows in this call
+    q_lens = np.array([3, 0, 6, 0, 4], np.int32)
+    cu = workloads.exclusive_offsets(q_lens)
+    rows = np.concatenate([np.arange(b.cu_q[i], b.cu_q[i] + q_lens[i]) for i in range(b.B)])
+    q = np.ascontiguousarray(b.q[rows])
+    o_ref, _ = oracle.verify_attention_kv8(q, k8, v8, ks, vs, b.block_tables, b.ctx_lens, cu, H_q=b.H_q, H_kv=b.H_kv, D=b.D,
+                                           P=b.P, scale=b.scale)
+    for n_wg in (0, 3):
+        out, _ = fsr.verify_attention_kv8(dev(q, True), dev(k8), dev(v8), dev(ks), dev(vs), dev(b.block_tables), dev(b.ctx_lens),
+                                          dev(cu), scale=b.scale, out_dtype=torch.float32, max_q_len=6, max_workgroups=n_wg)
+        torch.cuda.synchronize()
+        check_attention(out, o_ref, "bf16", len(rows))
+    # append: request 0's rows land past its last page when the table is cut to 2 pages (32 tokens, ctx = 40);
+    # request 2 points at a page outside the pool
+    bt = b.block_tables[:, :2].copy()
+    ctx = np.array([40, 7, 10, 0, 12], np.int32)
+    bt[2, 0] = b.n_pages + 5
+    rng = np.random.default_rng(9)
+    k_new = workloads.f32_to_bf16_bits(rng.standard_normal((len(rows), b.H_kv, b.D)).astype(np.float32))
+    v_new = workloads.f32_to_bf16_bits(rng.standard_normal((len(rows), b.H_kv, b.D)).astype(np.float32))
+    kc, vc = dev(k8), dev(v8)
+    fsr.kv_append_kv8(dev(k_new, True), dev(v_new, True), kc, vc, dev(ks), dev(vs), dev(bt), dev(ctx), dev(cu))
+    torch.cuda.synchronize()
+    bt_ref = bt.copy(); bt_ref[2, 0] = 0   # the oracle has no notion of a bad page id: drop request 2's rows instead
+    cu_ref_lens = q_lens.copy(); cu_ref_lens[2] = 0
+    keep = np.concatenate([np.arange(cu[i], cu[i] + cu_ref_lens[i]) for i in range(b.B)]).astype(int)
+    kc_ref, vc_ref = oracle.kv_append_kv8(k_new[keep], v_new[keep], k8, v8, ks, vs, bt_ref, ctx,
+                                          workloads.exclusive_offsets(cu_ref_lens), P=b.P)
+    assert np.array_equal(kc.cpu().numpy(), kc_ref) and np.array_equal(vc.cpu().numpy(), vc_ref)
+    assert (kc_ref != k8).any()     # request 4's rows did land
