@@ -222,3 +222,26 @@ def test_controller_rejects_bad_arguments(ctl):
         ctl.latency_fit(0, [1.0] * 3, [1.0] * 3, [0.5] * 3, [1.0] * 3)
     with pytest.raises(FsrError):
         ctl.chunk_size(ctl.latency_model(1, 1, 0, 1, 0, 1, 0, 1, 0), ctl.latency_model(1, 1, 0, 1, 0, 1, 0, 1, 0), 1, 0.5, 4, 1.0, [2])
+
+
+def test_oracle_gp_against_sklearn():
+    """The oracle's Gaussian-process posterior (Eq. 3's mu and sigma) against scikit-learn's regressor with the same
+    fixed kernel: an independent implementation of the same textbook formulas."""
+    from sklearn.gaussian_process import GaussianProcessRegressor
+    from sklearn.gaussian_process.kernels import RBF, ConstantKernel
+    rng = np.random.default_rng(8)
+    lengths = (2, 3, 4, 6, 8, 10, 12)
+    c = oc.Controller(lengths=lengths, window=40, eps=1e-3, length_scale=1.7, signal_var=1.3, noise_var=0.07)
+    for _ in range(25):
+        s = int(rng.choice(lengths))
+        c.observe(0, 5, s, int(rng.integers(0, s + 1)), float(1.0 + 0.2 * s + rng.random()))
+    mu, sigma = c.posterior(0, 5)
+    w = list(c.obs[0][5])
+    X = np.array([[o[0]] for o in w], dtype=np.float64)
+    y = np.array([o[3] for o in w])
+    mean, scale = y.mean(), y.std()
+    gp = GaussianProcessRegressor(kernel=ConstantKernel(1.3, "fixed") * RBF(1.7, "fixed"), alpha=0.07, optimizer=None,
+                                  normalize_y=False).fit(X, (y - mean) / scale)
+    pm, ps = gp.predict(np.array(lengths, dtype=np.float64)[:, None], return_std=True)
+    assert np.allclose(mu, mean + scale * pm, rtol=1e-9, atol=1e-12)
+    assert np.allclose(sigma, scale * ps, rtol=1e-6, atol=1e-9)
