@@ -5,7 +5,7 @@ Eqs. 1-2), the GP-LCB step (Eqs. 3-4), the pruning trigger (Sec. 3.2, Eqs. 5-10)
 (Sec. 3.3) and the latency models with a general-purpose non-linear least-squares fit (Sec. 3.4,
 Eqs. 11-14).  Shares no code with the C++ controller.
 
-Readings of what the paper leaves open (same as the product's, listed in the design notes): the window
+Readings of what the paper leaves open (the product makes the same ones): the window
 keeps the last W outcomes of a (context, request) pair; a_hat_i(s) averages that request's accepted
 fractions at s, T_hat(s) the latencies of every request of the context at s; the Gaussian process has a
 squared-exponential kernel on s, a constant prior mean equal to the window mean of the realised costs,
