@@ -170,3 +170,36 @@ def test_token_major_generic_path_and_append(fsr, oracle):
     torch.cuda.synchronize()
     kr, vr = oracle.kv_append(k_new, v_new, k_tm, v_tm, b.block_tables, b.ctx_lens, b.cu_q, P=b.P, token_major=True)
     assert np.array_equal(kc.cpu().numpy(), kr) and np.array_equal(vc.cpu().numpy(), vr)
+
+
+def test_alternating_caches_share_one_workspace(fsr, oracle):
+    """Many launches on one workspace with the cache contents swapped between two sets every time: a partial of a
+    cut item left over from the launch before (same slot, same shapes, other data) must never be picked up."""
+    announce("attention alternating caches on one workspace")
+    b = workloads.make_batch(2, rep=41, with_probs=False, ctx_lens=[3000, 2500, 1800, 2200, 900, 1400], spec_lens=[8, 3, 5, 1, 7, 2])
+    b2 = workloads.make_batch(2, rep=42, with_probs=False, ctx_lens=[3000, 2500, 1800, 2200, 900, 1400], spec_lens=[8, 3, 5, 1, 7, 2])
+    assert b2.k_cache.shape == b.k_cache.shape and not np.array_equal(b.k_cache, b2.k_cache)   # b's metadata serves both
+    d_bt, d_ctx, d_spec, d_cu = dev(b.block_tables), dev(b.ctx_lens), dev(b.spec_lens), dev(b.cu_q)
+    sets = [(dev(x.q, True), dev(x.k_cache, True), dev(x.v_cache, True)) for x in (b, b2)]
+    need = fsr.attn_workspace_bytes(B=b.B, N_cap=b.N, H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, max_pages=b.max_pages,
+                                    n_pages=b.n_pages, dtype=torch.bfloat16, out_dtype=torch.float32, max_q_len=b.S_max + 1)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    first = []
+    for q, k, v in sets:
+        out, _ = fsr.verify_attention(q, k, v, d_bt, d_ctx, d_spec, d_cu, scale=b.scale, out_dtype=torch.float32, workspace=ws,
+                                      max_q_len=b.S_max + 1)
+        first.append(out.clone())
+    torch.cuda.synchronize()
+    for x, o in zip((b, b2), first):
+        o_ref, _ = ref_of(oracle, b, q=x.q, k=x.k_cache, v=x.v_cache)
+        check_attention(o, o_ref, "bf16", b.N)
+    assert not torch.equal(first[0], first[1])
+    outs = [torch.empty_like(first[0]) for _ in range(2)]
+    for it in range(150):
+        s = it & 1
+        q, k, v = sets[s]
+        fsr.verify_attention(q, k, v, d_bt, d_ctx, d_spec, d_cu, scale=b.scale, out=outs[s], workspace=ws, max_q_len=b.S_max + 1)
+        if it % 10 >= 8:
+            torch.cuda.synchronize()
+            assert torch.equal(outs[s].view(torch.int32), first[s].view(torch.int32)), f"launch {it}"
+    torch.cuda.synchronize()
