@@ -66,7 +66,10 @@ constexpr int kQBytes = kMaxMT * 4 * 64 * 16;
 constexpr int kPrefOff = kQOff + kQBytes;
 constexpr int kPrefBytes = (kMaxB + 1) * 8;          // weighted tile prefix (64-bit)
 constexpr int kScanOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
-constexpr int kFastSmem = kScanOff + 64;
+// copies of the row offsets and context lengths the prefix has loaded anyway: the walker reads them here
+constexpr int kCuOff = kScanOff + 64;
+constexpr int kCtxOff = kCuOff + (kMaxB + 4) * 4;
+constexpr int kFastSmem = kCtxOff + kMaxB * 4;
 // Measured: a tile takes 2.0 / 2.4 / 2.5 us per wave with 1 / 2 / 3 query tiles riding on it (bandwidth, not the
 // matrix work, sets the pace), and taking up an item costs a workgroup 6 to 10 us of merge, count and refill.
 // Swept on four batches of the 16-request shape and on the 128- and 512-request shapes: base 3..6 with 12..20
@@ -163,7 +166,7 @@ __device__ __forceinline__ Group group_at(const FastArgs& a, int mt_max, int c, 
 __device__ __forceinline__ int rows_per_group(const FastArgs& a, int mt_max) { return max((16 * mt_max) / a.G, 1); }
 
 // Returns the largest per-tile cost of any item.
-__device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, long long* scratch) {
+__device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, long long* scratch, int* lds_cu, int* lds_ctx) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     long long carry = 0;
     int cmax = 1;
@@ -171,7 +174,11 @@ __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref,
         const int i = base + threadIdx.x;
         long long units = 0;
         if (i < a.B) {
-            const int ql = a.cu_q[i + 1] - a.cu_q[i], c = max(a.ctx[i], 0);
+            const int cu0 = a.cu_q[i], cu1 = a.cu_q[i + 1], c = max(a.ctx[i], 0);
+            const int ql = cu1 - cu0;
+            if (i == 0) lds_cu[0] = cu0;
+            lds_cu[i + 1] = cu1;
+            lds_ctx[i] = c;
             for (int j0 = 0; j0 < ql; j0 += rows_per_group(a, mt_max)) {
                 const Group gr = group_at(a, mt_max, c, ql, j0);
                 units += (long long)gr.nt * gr.cost;
@@ -332,6 +339,8 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
 // Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
 struct ShareWalker {
     const long long* pref;
+    const int* lds_cu;   // LDS copies of cu_q (B + 1 entries) and of max(ctx_lens, 0)
+    const int* lds_ctx;
     long long x, x1, T, q;
     int nb, r, b, mt_max;
     // what the segment just handed out is part of (for counting the pieces of a cut item)
@@ -357,9 +366,7 @@ struct ShareWalker {
             // scalar loads (constant address space, uniform index): they must not queue behind the K/V
             // tile loads that are in flight while the next segment is being looked up
             const int ri = uniform(locate_request(pref, a.B, a.H_kv, x));
-            const const_i32* cu = (const const_i32*)a.cu_q;
-            const const_i32* cx = (const const_i32*)a.ctx;
-            const int q0 = cu[ri], q_len = cu[ri + 1] - q0, c = max((int)cx[ri], 0);
+            const int q0 = uniform(lds_cu[ri]), q_len = uniform(lds_cu[ri + 1]) - q0, c = uniform(lds_ctx[ri]);
             // the KV head, then the row group, that hold position x
             const long long per_head = pref[ri + 1] - pref[ri], req_base = pref[ri] * a.H_kv;
             const int g = (int)div_u(x - req_base, per_head);
@@ -996,10 +1003,13 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
 #ifdef FSR_TIMING
     if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 126 * 4] = clock64();
 #endif
-    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + kScanOff));
+    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + kScanOff),
+                                       reinterpret_cast<int*>(smem + kCuOff), reinterpret_cast<int*>(smem + kCtxOff));
     FSR_STAMP(1);
     ShareWalker wk;
     wk.pref = pref;
+    wk.lds_cu = reinterpret_cast<const int*>(smem + kCuOff);
+    wk.lds_ctx = reinterpret_cast<const int*>(smem + kCtxOff);
     {
         // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
         // item then owns at least one of its tiles
