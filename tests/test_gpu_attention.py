@@ -203,3 +203,43 @@ def test_alternating_caches_share_one_workspace(fsr, oracle):
             torch.cuda.synchronize()
             assert torch.equal(outs[s].view(torch.int32), first[s].view(torch.int32)), f"launch {it}"
     torch.cuda.synchronize()
+
+
+def test_graph_of_launches_on_one_workspace_with_two_cache_sets(fsr, oracle):
+    """Eight launches captured in one HIP graph, odd and even ones over different cache contents, all on one
+    workspace; replayed with eager work in between, every replay bit-identical to the eager results."""
+    announce("attention graph with alternating caches")
+    lens = dict(ctx_lens=[2800, 2100, 1500, 3300, 700, 1900, 2600, 1200], spec_lens=[6, 2, 8, 0, 5, 3, 7, 1])
+    b = workloads.make_batch(2, rep=51, with_probs=False, **lens)
+    b2 = workloads.make_batch(2, rep=52, with_probs=False, **lens)
+    d_bt, d_ctx, d_spec, d_cu = dev(b.block_tables), dev(b.ctx_lens), dev(b.spec_lens), dev(b.cu_q)
+    sets = [(dev(x.q, True), dev(x.k_cache, True), dev(x.v_cache, True)) for x in (b, b2)]
+    need = fsr.attn_workspace_bytes(B=b.B, N_cap=b.N, H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, max_pages=b.max_pages,
+                                    n_pages=b.n_pages, dtype=torch.bfloat16, out_dtype=torch.bfloat16, max_q_len=b.S_max + 1)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty_like(sets[0][0]) for _ in range(8)]
+
+    def step():
+        for l in range(8):
+            q, k, v = sets[l & 1]
+            fsr.verify_attention(q, k, v, d_bt, d_ctx, d_spec, d_cu, scale=b.scale, out=outs[l], workspace=ws, max_q_len=b.S_max + 1)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step()
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in outs]
+        for x, o in zip((b, b2), eager[:2]):
+            o_ref, _ = ref_of(oracle, b, q=x.q, k=x.k_cache, v=x.v_cache)
+            check_attention(o, o_ref, "bf16", b.N)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            step()
+        for rep in range(12):
+            for o in outs:
+                o.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for l in range(8):
+                assert torch.equal(outs[l].view(torch.int16), eager[l].view(torch.int16)), (rep, l)
