@@ -145,7 +145,9 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
                 t_rows=None, d_rows=None, mode=PROBS, temperature=1.0, dtype="f32"):
     """Sec. 2.1 accept-until-first-mismatch with recovery/bonus token.
 
-    Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo[B], cdf_hi[B]).
+    Returns dict(accepted_len[B], n_emitted[B], emitted[B,S_max+1], cdf_lo[B], cdf_hi[B], tok_below[B],
+    tok_above[B]): the last four describe the drawn token's place in the row it was drawn from (its CDF
+    interval, and the nearest positive-mass token ids on either side, -1 if none).
     """
     if mode == GREEDY:
         return greedy_accept(p_target, draft_tokens, cu_t, cu_d, S_max=S_max, t_rows=t_rows, d_rows=d_rows)
@@ -163,13 +165,15 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     em = np.full((B, S_max + 1), -1, np.int32)
     lo = np.full(B, np.nan)
     hi = np.full(B, np.nan)
+    below = np.full(B, -1, np.int32)
+    above = np.full(B, -1, np.int32)
     rc = lib.fo_spec_accept(_p(p_target), _p(p_draft), _p(toks), _p(ua), _p(us), _p(cu_t), _p(cu_d), _p(tr), _p(dr),
-                            _p(acc), _p(nem), _p(em), _p(lo), _p(hi), ctypes.c_int(B), ctypes.c_int(V),
+                            _p(acc), _p(nem), _p(em), _p(lo), _p(hi), _p(below), _p(above), ctypes.c_int(B), ctypes.c_int(V),
                             ctypes.c_int(S_max), ctypes.c_int(mode), ctypes.c_double(temperature),
                             ctypes.c_int(F32 if dtype == "f32" else BF16))
     if rc != 0:
         raise ValueError(f"fo_spec_accept: {rc}")
-    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=lo, cdf_hi=hi)
+    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=lo, cdf_hi=hi, tok_below=below, tok_above=above)
 
 
 def greedy_accept(target, draft_tokens, cu_t, cu_d, *, S_max, t_rows=None, d_rows=None):
@@ -193,7 +197,8 @@ def greedy_accept(target, draft_tokens, cu_t, cu_d, *, S_max, t_rows=None, d_row
                               ctypes.c_int(B), ctypes.c_int(V), ctypes.c_int(S_max))
     if rc != 0:
         raise ValueError(f"fo_greedy_accept: {rc}")
-    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=np.full(B, np.nan), cdf_hi=np.full(B, np.nan))
+    return dict(accepted_len=acc, n_emitted=nem, emitted=em, cdf_lo=np.full(B, np.nan), cdf_hi=np.full(B, np.nan),
+                tok_below=np.full(B, -1, np.int32), tok_above=np.full(B, -1, np.int32))
 
 
 def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None):

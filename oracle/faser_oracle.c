@@ -209,9 +209,13 @@ static void row_probs(const void *rows, int dtype, int64_t r, int V, int mode, d
  * Inverse CDF over non-negative masses r[0..V): first token whose running sum (index
  * order) is strictly greater than u * R, R = sum r.  Zero-mass tokens are never chosen;
  * if rounding leaves no such token the last positive-mass token is taken.  Returns -1 if
- * R == 0.  cdf_lo/cdf_hi receive the chosen token's interval [F(t-1), F(t)] / R.
+ * R == 0.  cdf_lo/cdf_hi receive the chosen token's interval [F(t-1), F(t)] / R;
+ * tok_below/tok_above the nearest tokens of positive mass on either side of it (-1 if
+ * there is none): the only other tokens a draw at the very edge of the interval can
+ * reach.
  */
-static int inverse_cdf(const double *r, int V, double u, double *cdf_lo, double *cdf_hi)
+static int inverse_cdf(const double *r, int V, double u, double *cdf_lo, double *cdf_hi,
+                       int32_t *tok_below, int32_t *tok_above)
 {
     double R = 0.0;
     for (int v = 0; v < V; ++v)
@@ -220,23 +224,35 @@ static int inverse_cdf(const double *r, int V, double u, double *cdf_lo, double 
         return -1;
     const double thr = u * R;
     double c = 0.0;
-    int last_pos = -1;
+    int last_pos = -1, before_last = -1;
     double last_lo = 0.0;
     for (int v = 0; v < V; ++v) {
         const double prev = c;
         c += r[v];
         if (r[v] > 0.0) {
+            before_last = last_pos;
             last_pos = v;
             last_lo = prev;
             if (c > thr) {
                 if (cdf_lo) *cdf_lo = prev / R;
                 if (cdf_hi) *cdf_hi = c / R;
+                if (tok_below) *tok_below = before_last;
+                if (tok_above) {
+                    *tok_above = -1;
+                    for (int w = v + 1; w < V; ++w)
+                        if (r[w] > 0.0) {
+                            *tok_above = w;
+                            break;
+                        }
+                }
                 return v;
             }
         }
     }
     if (cdf_lo) *cdf_lo = last_lo / R;
     if (cdf_hi) *cdf_hi = 1.0;
+    if (tok_below) *tok_below = before_last;
+    if (tok_above) *tok_above = -1;
     return last_pos;
 }
 
@@ -257,14 +273,17 @@ static int inverse_cdf(const double *r, int V, double u, double *cdf_lo, double 
  * Tokens are drawn by inverse CDF with the single u_sample[i].
  *
  * emitted is [B, S_max+1] padded with -1.  cdf_lo/cdf_hi (nullable, [B]) give the drawn
- * token's CDF interval (NaN if no token was drawn).  The rows are fp32, or bf16 bit patterns
+ * token's CDF interval (NaN if no token was drawn), tok_below/tok_above (nullable, [B]) the
+ * nearest positive-mass tokens on either side of it in the row it was drawn from (-1 if
+ * none, or if no token was drawn).  The rows are fp32, or bf16 bit patterns
  * (dtype), a bf16 value being the fp32 value with the same leading bits.
  */
 int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *draft_tokens,
                    const float *u_accept, const float *u_sample, const int32_t *cu_t,
                    const int32_t *cu_d, const int32_t *t_rows, const int32_t *d_rows,
                    int32_t *accepted_len, int32_t *n_emitted, int32_t *emitted, double *cdf_lo,
-                   double *cdf_hi, int B, int V, int S_max, int mode, double temperature, int dtype)
+                   double *cdf_hi, int32_t *tok_below, int32_t *tok_above, int B, int V, int S_max, int mode,
+                   double temperature, int dtype)
 {
     int status = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -276,6 +295,8 @@ int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *dra
             em[s] = -1;
         if (cdf_lo) cdf_lo[i] = NAN;
         if (cdf_hi) cdf_hi[i] = NAN;
+        if (tok_below) tok_below[i] = -1;
+        if (tok_above) tok_above[i] = -1;
         accepted_len[i] = 0;
         n_emitted[i] = 0;
         if (d_i > S_max || t_i < d_i || t_i > d_i + 1) {
@@ -318,13 +339,16 @@ int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *dra
                 const double r = p[v] - qv[v];
                 qv[v] = r > 0.0 ? r : 0.0;
             }
-            tok = inverse_cdf(qv, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0);
+            tok = inverse_cdf(qv, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0,
+                              tok_below ? tok_below + i : 0, tok_above ? tok_above + i : 0);
             if (tok < 0)
-                tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0);
+                tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0,
+                              tok_below ? tok_below + i : 0, tok_above ? tok_above + i : 0);
         } else if (t_i == d_i + 1) { /* everything accepted: bonus token from the extra target row */
             const int64_t tr = t_rows ? t_rows[cu_t[i] + d_i] : cu_t[i] + d_i;
             row_probs(p_target, dtype, tr, V, mode, temperature, p);
-            tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0);
+            tok = inverse_cdf(p, V, (double)u_sample[i], cdf_lo ? cdf_lo + i : 0, cdf_hi ? cdf_hi + i : 0,
+                              tok_below ? tok_below + i : 0, tok_above ? tok_above + i : 0);
         }
         if (tok >= 0) {
             em[n] = tok;
@@ -346,6 +370,8 @@ int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *dra
  *
  * `target` is [rows, V] fp32, probabilities or logits alike: only the position of the row
  * maximum matters.  The arg-max of a row is the LOWEST token id holding the row's maximum.
+ * A NaN score never wins against a number: it counts as minus infinity (so a row of NaN
+ * alone yields token 0).
  * Row layout, t_rows / d_rows maps and outputs as in fo_spec_accept; no uniforms, no draft
  * distributions.
  *
@@ -354,11 +380,16 @@ int fo_spec_accept(const void *p_target, const void *p_draft, const int32_t *dra
  *   all accepted and t_i = d_i + 1: token = argmax(target row d_i)
  *   all accepted and t_i = d_i: no extra token
  */
+static double greedy_score(float x)
+{
+    return x != x ? -INFINITY : (double)x;
+}
+
 static int argmax_row(const float *rows, int64_t r, int V)
 {
     int best = 0;
     for (int v = 1; v < V; ++v)
-        if ((double)rows[r * V + v] > (double)rows[r * V + best])
+        if (greedy_score(rows[r * V + v]) > greedy_score(rows[r * V + best]))
             best = v;
     return best;
 }

@@ -22,9 +22,11 @@ constexpr int kChunk = 4096;  // scores per workgroup
 
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
-// fp32 bits -> unsigned integer with the same order (-0 and +0 map to the same key).
+// fp32 bits -> unsigned integer with the same order (-0 and +0 map to the same key; a NaN never wins
+// against a number: it takes the key of minus infinity).
 __device__ __forceinline__ uint32_t ordered_bits(uint32_t b) {
     if ((b << 1) == 0) b = 0;  // -0 -> +0
+    if ((b & 0x7fffffffu) > 0x7f800000u) b = 0xff800000u;  // NaN -> -inf
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 __device__ __forceinline__ unsigned long long make_key(uint32_t bits, int idx) {

@@ -51,7 +51,7 @@ def test_vocab_sizes_and_ragged_tail(fsr, oracle, V):
                              spec_lens=[0, 1, 2, 3, 4, 5, 6, 7, 8, 1, 2, 3] * 2, ctx_lens=[10] * 24)
     (frag, mism), ref = run_pair(fsr, oracle, b)
     print(f"V={V}: fragile={frag} mismatches={mism}")
-    assert mism <= frag
+    assert mism == 0
     assert 0 < (ref["accepted_len"] < b.spec_lens).sum() < b.B
 
 
@@ -60,7 +60,7 @@ def test_config2_full_vocab(fsr, oracle):
     b = workloads.make_batch(2, with_kv=False)
     (frag, mism), ref = run_pair(fsr, oracle, b)
     print(f"config2: fragile={frag} mismatches={mism} accepted={ref['accepted_len'].sum()}/{b.spec_lens.sum()}")
-    assert mism <= frag
+    assert mism == 0
 
 
 def test_no_bonus_rows_and_row_maps(fsr, oracle):
@@ -122,7 +122,7 @@ def test_logits_mode(fsr, oracle, T):
                              ctx_lens=[10] * 12, keep_logits=True)
     (frag, mism), ref = run_pair(fsr, oracle, b, mode=1, temperature=T)
     print(f"LOGITS T={T}: fragile={frag} mismatches={mism}")
-    assert mism <= frag
+    assert mism == 0
 
 
 def test_invalid_request_is_flagged_not_faulted(fsr, oracle):
@@ -152,5 +152,5 @@ def test_bf16_rows(fsr, oracle, mode, V):
     torch.cuda.synchronize()
     frag, mism = check_accept(gpu, ref, b.u_sample)
     print(f"bf16 rows mode={mode} V={V}: fragile={frag} mismatches={mism}")
-    assert mism <= frag
+    assert mism == 0
     assert 0 < ref["accepted_len"].sum() < b.N_d

@@ -54,6 +54,32 @@ def test_vocab_sizes_ties_and_misaligned_rows(fsr, oracle, V):
         assert (ref["accepted_len"] < spec).any()
 
 
+def test_nan_scores_count_as_minus_infinity(fsr, oracle):
+    """NaN scores never win the arg-max (they count as -inf; ties to the lowest id), on rows long enough to span
+    several workgroups with the NaNs in different chunks."""
+    announce("greedy accept with NaN scores")
+    rng = np.random.default_rng(77)
+    V = 9001
+    spec = np.array([3, 0, 2, 5, 1], np.int32)
+    cu_t, cu_d = workloads.exclusive_offsets(spec + 1), workloads.exclusive_offsets(spec)
+    z = rng.standard_normal((int(cu_t[-1]), V)).astype(np.float32)
+    z[rng.random(z.shape) < 0.05] = np.nan
+    z[0, 0] = np.nan                      # a NaN in front of the row
+    z[1] = np.nan                         # a row of NaN alone -> token 0
+    z[2] = -np.inf
+    z[2, ::3] = np.nan                    # NaN and -inf tie -> lowest id
+    z[3, :4500] = np.nan                  # whole first chunk NaN
+    z[4, 5000] = np.inf
+    z[4, 7000] = np.nan
+    toks = rng.integers(0, V, size=int(cu_d[-1])).astype(np.int32)
+    clean = np.where(np.isnan(z), -np.inf, z)
+    for i, s in enumerate(spec):
+        for j in range(max(int(s) - (i % 2), 0)):
+            toks[cu_d[i] + j] = int(np.argmax(clean[cu_t[i] + j]))
+    ref = _compare(fsr, oracle, z, toks, cu_t, cu_d, 5)
+    assert ref["emitted"][1, 0] == 0 and ref["accepted_len"].sum() > 0
+
+
 def test_config2_full_vocab_and_row_maps(fsr, oracle):
     announce("greedy accept config2 full vocabulary, with row maps")
     b = workloads.make_batch(2, rep=2, with_kv=False, keep_logits=True)

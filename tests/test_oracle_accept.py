@@ -277,3 +277,37 @@ def test_bf16_rows_equal_their_widened_fp32_rows(oracle, mode):
     for k in ("accepted_len", "n_emitted", "emitted"):
         assert np.array_equal(ref[k], got[k]), k
     assert np.array_equal(ref["cdf_lo"], got["cdf_lo"], equal_nan=True)
+
+
+def test_neighbour_tokens_of_the_drawn_token(oracle):
+    """tok_below / tok_above: nearest positive-mass ids around the drawn token, written out by hand on
+    rows with zero-mass gaps (bonus draw from p, so the mass row is the target row itself)."""
+    p = np.array([[0.25, 0.0, 0.25, 0.0, 0.5, 0.0],      # u = 0.3  -> token 2, neighbours 0 and 4
+                  [0.0, 0.5, 0.0, 0.0, 0.5, 0.0],        # u = 0.1  -> token 1, nothing below, 4 above
+                  [0.0, 0.5, 0.0, 0.0, 0.5, 0.0],        # u = 0.9  -> token 4, 1 below, nothing above
+                  [0.0, 0.0, 1.0, 0.0, 0.0, 0.0]], np.float32)   # one-hot: no neighbours
+    u = np.array([0.3, 0.1, 0.9, 0.5], np.float32)
+    cu_t = np.arange(5, dtype=np.int32)
+    cu_d = np.zeros(5, np.int32)
+    r = oracle.spec_accept(p, np.zeros((0, 6), np.float32), np.zeros(0, np.int32), np.zeros(0, np.float32), u, cu_t, cu_d,
+                           S_max=0)
+    assert r["emitted"][:, 0].tolist() == [2, 1, 4, 2]
+    assert r["tok_below"].tolist() == [0, -1, 1, -1]
+    assert r["tok_above"].tolist() == [4, 4, -1, -1]
+    # brute force on random sparse rows
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        V = int(rng.integers(2, 12))
+        row = rng.random(V) * (rng.random(V) < 0.6)
+        if row.sum() == 0:
+            row[rng.integers(V)] = 1.0
+        row = (row / row.sum()).astype(np.float32)[None]
+        uu = np.array([rng.random()], np.float32)
+        r = oracle.spec_accept(row, np.zeros((0, V), np.float32), np.zeros(0, np.int32), np.zeros(0, np.float32), uu,
+                               np.array([0, 1], np.int32), np.zeros(2, np.int32), S_max=0)
+        t = int(r["emitted"][0, 0])
+        pos = np.flatnonzero(row[0] > 0)
+        k = int(np.searchsorted(pos, t))
+        assert pos[k] == t
+        assert r["tok_below"][0] == (pos[k - 1] if k > 0 else -1)
+        assert r["tok_above"][0] == (pos[k + 1] if k + 1 < len(pos) else -1)

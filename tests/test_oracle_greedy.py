@@ -115,3 +115,23 @@ def test_row_maps_and_chunked_equals_one_shot(oracle):
     inv = np.argsort(perm).astype(np.int32)
     mapped = oracle.greedy_accept(b.z_target[perm], b.draft_tokens, b.cu_q, b.cu_d, S_max=b.S_max, t_rows=inv)
     assert np.array_equal(mapped["emitted"], one["emitted"])
+
+
+def test_nan_scores_never_win(oracle):
+    """A NaN score counts as minus infinity: it loses to every number, ties with -inf resolve to the lowest id,
+    a row of NaN alone yields token 0."""
+    nan, inf = np.nan, np.inf
+    z = np.array([[nan, 1.0, 3.0, nan, 3.0],      # NaN in front must not shadow the maximum: 2
+                  [nan, nan, nan, nan, nan],      # 0
+                  [-inf, nan, -inf, nan, -inf],   # all equal after the rule: 0
+                  [nan, -inf, -5.0, nan, -inf],   # 2
+                  [2.0, nan, 2.0, 1.0, nan]], np.float32)   # 0
+    cu_t = np.arange(6, dtype=np.int32)
+    cu_d = np.zeros(6, np.int32)
+    r = oracle.greedy_accept(z, np.zeros(0, np.int32), cu_t, cu_d, S_max=0)
+    assert r["emitted"][:, 0].tolist() == [2, 0, 0, 2, 0]
+    # the same rows as drafts' targets: a draft equal to that arg-max is accepted, any other is not
+    toks = np.array([2, 1, 0, 2, 4], np.int32)
+    r = oracle.greedy_accept(np.concatenate([z, z[:0]]), toks, cu_t, np.arange(6, dtype=np.int32), S_max=1)
+    assert r["accepted_len"].tolist() == [1, 0, 1, 1, 0]
+    assert np.array_equal(np.nanargmax(np.where(np.isnan(z[[0, 3, 4]]), -inf, z[[0, 3, 4]]), axis=1), [2, 2, 0])
