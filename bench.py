@@ -45,7 +45,7 @@ WORKLOADS = {
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
 
 
-def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9):
+def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=True):
     """Device buffers and a closure running one full step without allocating.  The layers cycle
     through as many distinct KV caches as fit the budget (all 32 at workload 2)."""
     def dev(x, bf16=False):
@@ -90,16 +90,20 @@ def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9):
                      active_ids=torch.empty(b.B, **i32))
     packed = torch.empty_like(out)
 
+    plan = fsr.attn_plan(q, k0, bt, ctx, cu_q, scale=b.scale, max_q_len=S_max + 1) if use_plan else None
+
     def attention_all_layers():
+        # the step's schedule once (lengths and block tables are the same for every layer), then the layers
+        if use_plan:
+            fsr.attn_plan(q, k0, bt, ctx, cu_q, scale=b.scale, max_q_len=S_max + 1, plan=plan)
         for l in range(n_layers):
             fsr.verify_attention(q, k_caches[l % n_caches], v_caches[l % n_caches], bt, ctx, spec, cu_q, scale=b.scale,
-                                 out=out, workspace=ws_attn, max_q_len=S_max + 1)
+                                 out=out, workspace=ws_attn, max_q_len=S_max + 1, plan=plan)
 
     def tail():
         fsr.spec_accept(p_t, p_d, toks, u_a, u_s, cu_q, cu_d, S_max=S_max, accepted_len=acc, n_emitted=nem, emitted=em,
                         workspace=ws_acc)
-        fsr.survivor_mask(acc, cu_q, keep)
-        fsr.prune_compact(keep, cu_q, suffix_close=True, payload=out, payload_out=packed, out=prune_out)
+        fsr.survivor_compact(acc, cu_q, b.N, keep_mask=keep, payload=out, payload_out=packed, out=prune_out)
 
     def step():
         attention_all_layers()
@@ -246,6 +250,9 @@ def main():
                          "run the same one-shot step at their batch shapes")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-plan", action="store_true",
+                    help="every attention launch rebuilds the step's schedule itself (fsr_verify_attention) instead of "
+                         "reading the per-step plan (fsr_attn_plan + fsr_verify_attention_planned)")
     ap.add_argument("--overlap", type=int, default=0, metavar="N",
                     help="also measure the step's attention on a stream that owns all but N compute units next to a "
                          "stand-in drafter on a stream that owns those N (adds an \"overlap\" object to the JSON line)")
@@ -264,7 +271,7 @@ def main():
     fsr.load_library()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
     b = workloads.make_batch(args.workload)
-    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002)
+    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=not args.no_plan)
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")

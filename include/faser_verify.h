@@ -19,7 +19,10 @@
  *     workspace.  Nothing is allocated or freed by these calls.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  No call synchronises the stream or the device.  Calls on one stream may
- *     share a workspace; calls that can overlap on different streams must not.
+ *     share a workspace; calls that can overlap in time (different streams, or graphs replayed
+ *     on different streams) must not: at most one call may be in flight per workspace.  (The
+ *     attention kernel tags what it leaves there with the call's id: a slot written by another
+ *     call turns the affected output rows into NaN instead of being summed silently.)
  *   - Ragged metadata (lengths, offsets, masks) lives on the device; the only host scalars
  *     are static shapes and capacities.  Host-detectable errors (null pointers, bad
  *     shapes, unsupported dtype/head_dim, workspace too small) are reported before
@@ -150,6 +153,42 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
                          void* stream);
 
 /*
+ * Which kernel fsr_verify_attention runs for shapes *p (host query, no GPU work): FSR_PATH_STREAM,
+ * the HBM-bandwidth kernel (bf16, D = 128, P = 16, H_q / H_kv <= 16, B <= 4096), or
+ * FSR_PATH_GENERIC, one wavefront per (row, head) for every other supported shape (fp32 inputs,
+ * D = 64, other page sizes, wider groups, larger batches): correct, but it re-reads K/V per query
+ * head and row and is many times slower on large batches.  Negative on invalid shapes.
+ */
+#define FSR_PATH_GENERIC 0
+#define FSR_PATH_STREAM 1
+int fsr_attn_path(const fsr_attn_params* p /*host*/);
+
+/*
+ * Per-step schedule of the attention calls (Sec. 3.1: the batch of a verification step, with its
+ * per-request speculative lengths, is fixed before the target model runs; every transformer layer
+ * then sees the same lengths, row offsets and block tables).  fsr_attn_plan builds, once per step,
+ * what every fsr_verify_attention call would otherwise rebuild at the start of its launch: the split
+ * of the batch's K/V tiles over the workgroups and, per workgroup, the pages of its first tiles.
+ * fsr_verify_attention_planned is fsr_verify_attention reading that schedule; the two give
+ * bit-identical results.
+ *
+ *   plan        device buffer of >= fsr_attn_plan_bytes(p) bytes, 16-byte aligned, written by
+ *               fsr_attn_plan (asynchronously, on `stream`) and read by the planned calls enqueued
+ *               behind it.  It stays valid while block_tables, ctx_lens and cu_q keep their
+ *               contents; *p must be the same in both calls (out_dtype, scale and kv_layout may
+ *               differ), else the planned call returns FSR_ESHAPE / FSR_EINVAL before launching.
+ * Only shapes with fsr_attn_path(p) == FSR_PATH_STREAM can be planned (FSR_EUNSUP otherwise).
+ */
+int fsr_attn_plan_bytes(const fsr_attn_params* p /*host*/, size_t* out_bytes /*host*/);
+int fsr_attn_plan(const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q,
+                  const fsr_attn_params* p /*host*/, void* plan, size_t plan_bytes, void* stream);
+int fsr_verify_attention_planned(const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* block_tables, const int32_t* ctx_lens,
+                                 const int32_t* cu_q, void* out, float* lse,
+                                 const fsr_attn_params* p /*host*/, const void* plan, void* workspace,
+                                 size_t ws_bytes, void* stream);
+
+/*
  * Cache append (Sec. 2.1 / Sec. 3.1, as fsr_kv_append) into caches stored in 8 bits: element x of a bf16 key
  * row of KV head g is stored as the E4M3 byte nearest to fl32(x / k_scale[g]) (ties to the even code, magnitudes
  * beyond 448 saturate, NaN stays NaN); values likewise with v_scale.  fsr_verify_attention_kv8 reads them back as
@@ -266,8 +305,8 @@ int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, int32_t* ne
                       size_t row_bytes, const fsr_prune_params* p /*host*/, void* stream);
 
 /*
- * Inverse of the compaction (Sec. 3.2: pruned positions are restored to the original
- * layout before logits; Sec. 4: pruned tensors are padded back to their original shapes).
+ * Inverse of the compaction (Sec. 3.2 / Sec. 4: what was pruned away inside the model must be
+ * back at its original row before the logits are formed, with filler in the rows that were dropped).
  * restored[r] = compact[dst_row[r]] where dst_row[r] >= 0, else every 32-bit word of the
  * row is pad_word; has_value[r] (nullable, uint8) says which.  row_bytes % 4 == 0.
  */
@@ -276,10 +315,9 @@ int fsr_prune_restore(const void* compact, const int32_t* dst_row, void* restore
                       void* stream);
 
 /*
- * Early-exit rank check (Sec. 3.2: a drafted token that falls outside the Top-K set of the
- * intermediate logits is marked unlikely to be accepted and becomes a pruning candidate; Sec. 4:
- * the Top-K set is not materialised, it is only checked whether at least K tokens exceed the
- * drafted token's score).
+ * Early-exit rank check (Sec. 3.2: intermediate scores predict a rejection when the draft is not
+ * among their K best tokens; Sec. 4: that is decided by counting the scores above the draft's own,
+ * without ever building the set of the K best).
  *
  * Request i owns the score rows cu_q[i] .. cu_q[i+1]-1 (its active query rows, q_i of them) and the
  * drafts cu_d[i] .. cu_d[i+1]-1 (d_i of them).  Row j scores the token that follows the row's
@@ -309,6 +347,19 @@ int fsr_topk_rank_check(const void* logits, const int32_t* draft_tokens, const i
  */
 int fsr_survivor_mask(const int32_t* accepted_len, const int32_t* cu_q, uint8_t* keep_mask, int32_t B,
                       int32_t N_cap, void* stream);
+
+/*
+ * fsr_survivor_mask followed by fsr_prune_compact (suffix_close = 1) in one call and one launch
+ * less (Sec. 2.1 / Sec. 3.2: after the accept step the rejected suffix of every request is dropped
+ * and the survivors are re-packed): request i keeps its rows 0 .. accepted_len[i].  keep_mask
+ * [N_cap] uint8 is an optional OUTPUT here (the mask fsr_survivor_mask would have written; may be
+ * null); every other argument as in fsr_prune_compact (p->suffix_close is ignored).
+ */
+int fsr_survivor_compact(const int32_t* accepted_len, const int32_t* cu_q, uint8_t* keep_mask,
+                         int32_t* new_cu_q, int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row,
+                         int32_t* n_active, int32_t* active_ids, const void* payload_in,
+                         void* payload_out, size_t row_bytes, const fsr_prune_params* p /*host*/,
+                         void* stream);
 
 /*
  * Partial restore (Sec. 3.2, same passage): out[src_row[r]] = compact[r] for r < n_rows[0];

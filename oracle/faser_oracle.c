@@ -38,12 +38,11 @@
  *   fo_prune_compact     Sec. 3.2: rows predicted/observed to be in the rejected suffix
  *                        are pruned and only the remaining rows proceed; Sec. 3.3: on a
  *                        rejection every speculative token beyond it is discarded.
- *   fo_prune_restore     Sec. 3.2 / Sec. 4: pruned positions are padded back to the
- *                        original layout; pruned rows carry no values.
- *   fo_topk_rank_check   Sec. 3.2: a drafted token outside the Top-K set of the
- *                        intermediate logits becomes a pruning candidate; Sec. 4: the
- *                        Top-K set is not materialised, it is only checked whether at
- *                        least K tokens exceed the drafted token's score.
+ *   fo_prune_restore     Sec. 3.2 / Sec. 4: survivors return to their original rows,
+ *                        dropped rows get filler and carry no values.
+ *   fo_topk_rank_check   Sec. 3.2: intermediate scores predict a rejection when the
+ *                        draft is not among their K best tokens; Sec. 4: decided by
+ *                        counting the scores above the draft's own.
  */
 #include <math.h>
 #include <stdint.h>
@@ -494,8 +493,8 @@ int fo_prune_compact(const uint8_t *keep_mask, const int32_t *cu_q, int32_t *new
 
 /*
  * Inverse of the compaction: rows go back to their original positions; pruned rows are
- * filled with the byte `pad` and flagged 0 in has_value (Sec. 3.2: pruned tokens have no
- * logits; Sec. 4: pruned tensors are padded back to their original shapes).
+ * filled with the byte `pad` and flagged 0 in has_value (Sec. 3.2 / Sec. 4: a dropped row has
+ * no scores of its own; the original shape comes back with filler in its place).
  */
 int fo_prune_restore(const uint8_t *compact, const int32_t *dst_row, uint8_t *restored,
                      uint8_t *has_value, int64_t row_bytes, int N, int pad)

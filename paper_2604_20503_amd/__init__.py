@@ -8,6 +8,8 @@ does, and fails loudly if it has not been built (``python paper_2604_20503_amd/b
 from .binding import (  # noqa: F401
     FsrError,
     accept_workspace_bytes,
+    attn_path,
+    attn_plan,
     attn_workspace_bytes,
     frontier_commit,
     frontier_init,
@@ -21,6 +23,7 @@ from .binding import (  # noqa: F401
     prune_restore,
     prune_scatter,
     spec_accept,
+    survivor_compact,
     survivor_mask,
     topk_rank_check,
     verify_attention,
@@ -30,7 +33,7 @@ from .binding import (  # noqa: F401
 from .frontier import verify_chunked  # noqa: F401
 
 __all__ = [
-    "FsrError", "accept_workspace_bytes", "attn_workspace_bytes", "frontier_commit", "frontier_init",
+    "FsrError", "accept_workspace_bytes", "attn_path", "attn_plan", "attn_workspace_bytes", "frontier_commit", "frontier_init",
     "frontier_plan", "kv_append", "kv_append_kv8", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
-    "spec_accept", "survivor_mask", "topk_rank_check", "verify_attention", "verify_attention_kv8", "verify_chunked", "version",
+    "spec_accept", "survivor_compact", "survivor_mask", "topk_rank_check", "verify_attention", "verify_attention_kv8", "verify_chunked", "version",
 ]

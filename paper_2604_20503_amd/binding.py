@@ -21,9 +21,10 @@ PROBS, LOGITS, GREEDY = 0, 1, 2
 KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
 
 SYMBOLS = [
-    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
+    "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_attn_path", "fsr_attn_plan_bytes", "fsr_attn_plan",
+    "fsr_verify_attention_planned", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
-    "fsr_prune_scatter", "fsr_survivor_mask", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
+    "fsr_prune_scatter", "fsr_survivor_mask", "fsr_survivor_compact", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
 
 
@@ -136,11 +137,43 @@ def attn_workspace_bytes(*, B, N_cap, H_q, H_kv, D, P, max_pages, n_pages, dtype
     return int(out.value)
 
 
+PATH_GENERIC, PATH_STREAM = 0, 1
+
+
+def attn_path(*, B, N_cap, H_q, H_kv, D, P, max_pages, n_pages, dtype, out_dtype, max_q_len=0) -> int:
+    """fsr_attn_path: PATH_STREAM (the bandwidth kernel) or PATH_GENERIC (one wavefront per row and head)."""
+    p = AttnParams(B=B, N_cap=N_cap, H_q=H_q, H_kv=H_kv, D=D, P=P, max_pages=max_pages, n_pages=n_pages,
+                   dtype=_code(dtype), out_dtype=_code(out_dtype), scale=1.0, max_q_len=int(max_q_len),
+                   max_workgroups=0, kv_layout=0)
+    rc = load_library().fsr_attn_path(ctypes.byref(p))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def attn_plan(q, k_cache, block_tables, ctx_lens, cu_q, *, scale, out_dtype=None, max_q_len=0, max_workgroups=0,
+              kv_layout=KV_HEAD_MAJOR, plan=None):
+    """fsr_attn_plan: build the step's schedule (device buffer, returned) for verify_attention(..., plan=...).
+    q and k_cache are looked at for their shapes only."""
+    lib = load_library()
+    B = ctx_lens.shape[0]
+    p = _attn_params(q, k_cache, block_tables, B, out_dtype or q.dtype, scale, max_q_len, max_workgroups, kv_layout)
+    need = ctypes.c_size_t(0)
+    _check(lib.fsr_attn_plan_bytes(ctypes.byref(p), ctypes.byref(need)))
+    if plan is None:
+        plan = torch.empty(max(need.value, 16), dtype=torch.uint8, device=q.device)
+    _check(lib.fsr_attn_plan(_ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+                             _ptr(cu_q, torch.int32, "cu_q"), ctypes.byref(p), _ptr(plan, name="plan"),
+                             ctypes.c_size_t(plan.numel() * plan.element_size()), _stream()))
+    return plan
+
+
 def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_q, *, scale, out=None, lse=None,
-                     out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR):
+                     out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR, plan=None):
     """fsr_verify_attention.  q [N_cap,H_q,D]; caches [n_pages,H_kv,P,D]; returns (out, lse).
     max_workgroups: size of the persistent grid when the current stream owns only part of the device.
-    kv_layout: KV_HEAD_MAJOR (caches [n_pages,H_kv,P,D]) or KV_TOKEN_MAJOR (caches [n_pages,P,H_kv,D])."""
+    kv_layout: KV_HEAD_MAJOR (caches [n_pages,H_kv,P,D]) or KV_TOKEN_MAJOR (caches [n_pages,P,H_kv,D]).
+    plan: buffer from attn_plan for the same shapes and metadata -> fsr_verify_attention_planned."""
     lib = load_library()
     B = ctx_lens.shape[0]
     out_dtype = out_dtype or (out.dtype if out is not None else q.dtype)
@@ -156,6 +189,13 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
     if workspace is None and need.value:
         workspace = torch.empty(need.value, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if plan is not None:
+        _check(lib.fsr_verify_attention_planned(
+            _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+            _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+            _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"), _ptr(lse, torch.float32, "lse"), ctypes.byref(p),
+            _ptr(plan, name="plan"), _ptr(workspace, name="workspace"), ctypes.c_size_t(ws_bytes), _stream()))
+        return out, lse
     _check(lib.fsr_verify_attention(
         _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
         _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
@@ -273,11 +313,21 @@ def spec_accept(p_target, p_draft, draft_tokens, u_accept, u_sample, cu_t, cu_d,
     return accepted_len, n_emitted, emitted
 
 
-def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None, payload_out=None, out=None):
-    """fsr_prune_compact.  Returns dict(new_cu_q, new_q_lens, src_row, dst_row, n_active, active_ids[, payload])."""
+def survivor_compact(accepted_len, cu_q, N_cap, *, keep_mask=None, payload=None, payload_out=None, out=None):
+    """fsr_survivor_compact: rows 0..accepted_len[i] of every request survive and are re-packed (keep_mask, if
+    given, receives the mask).  Returns the dict of prune_compact."""
+    return prune_compact(keep_mask, cu_q, suffix_close=True, payload=payload, payload_out=payload_out, out=out,
+                         accepted_len=accepted_len, N_cap=N_cap)
+
+
+def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None, payload_out=None, out=None, accepted_len=None,
+                  N_cap=None):
+    """fsr_prune_compact.  Returns dict(new_cu_q, new_q_lens, src_row, dst_row, n_active, active_ids[, payload]).
+    With accepted_len (and N_cap) it is fsr_survivor_compact and keep_mask an optional output."""
     lib = load_library()
     B = cu_q.shape[0] - 1
-    N_cap = keep_mask.shape[0]
+    if N_cap is None:
+        N_cap = keep_mask.shape[0]
     dev = cu_q.device
     p = PruneParams(B=B, N_cap=N_cap, suffix_close=1 if suffix_close else 0, reserved=0)
     o = out or {}
@@ -297,6 +347,19 @@ def prune_compact(keep_mask, cu_q, *, suffix_close=True, payload=None, payload_o
         row_bytes = (payload.numel() // max(N_cap, 1)) * payload.element_size() if N_cap else 0
         if payload_out is None:
             payload_out = torch.empty_like(payload)
+    if accepted_len is not None:
+        _check(lib.fsr_survivor_compact(
+            _ptr(accepted_len, torch.int32, "accepted_len"), _ptr(cu_q, torch.int32, "cu_q"),
+            _ptr(keep_mask, torch.uint8, "keep_mask"), _ptr(new_cu_q, torch.int32),
+            _ptr(new_q_lens, torch.int32), _ptr(src_row, torch.int32), _ptr(dst_row, torch.int32),
+            _ptr(n_active, torch.int32), _ptr(active_ids, torch.int32),
+            _ptr(payload if row_bytes else None, name="payload"), _ptr(payload_out if row_bytes else None, name="payload_out"),
+            ctypes.c_size_t(row_bytes), ctypes.byref(p), _stream()))
+        res = dict(new_cu_q=new_cu_q, new_q_lens=new_q_lens, src_row=src_row, dst_row=dst_row, n_active=n_active,
+                   active_ids=active_ids)
+        if payload is not None:
+            res["payload"] = payload_out
+        return res
     _check(lib.fsr_prune_compact(
         _ptr(keep_mask, torch.uint8, "keep_mask"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(new_cu_q, torch.int32),
         _ptr(new_q_lens, torch.int32), _ptr(src_row, torch.int32), _ptr(dst_row, torch.int32),

@@ -12,6 +12,9 @@ namespace fsr {
 
 char* error_buffer();  // thread-local, 256 bytes
 
+// A number no earlier call of this process has used (48 bits, never 0): tags what a call leaves in a workspace.
+unsigned long long next_call_id();
+
 inline int fail(int code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);

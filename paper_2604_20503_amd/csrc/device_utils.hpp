@@ -1,4 +1,5 @@
-// Wavefront-level (64 lanes) reductions and scans used by the accept and prune kernels.
+// Wavefront-level (64 lanes) reductions and scans, and the arrival counter several kernels use to
+// find out which workgroup is the last of a group to finish.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -40,6 +41,20 @@ __device__ __forceinline__ T wave_inclusive_scan(T v) {
         if (lane >= o) v += up;
     }
     return v;
+}
+
+// Count one more arrival on a 64-bit word that holds (call id << 16 | count).  A word left by another
+// call (or never written) counts as zero, so the memory it lives in needs no clearing between calls
+// and HIP-graph replays work.  Returns the count including this arrival.  Device scope.
+__device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned long long call_id) {
+    unsigned long long seen = __atomic_load_n(word, __ATOMIC_RELAXED);
+    for (;;) {
+        const unsigned long long have = (seen >> 16) == call_id ? (seen & 0xffffu) : 0u;
+        const unsigned long long want = (call_id << 16) | (have + 1);
+        const unsigned long long prev = atomicCAS(word, seen, want);
+        if (prev == seen) return (int)(have + 1);
+        seen = prev;
+    }
 }
 
 }  // namespace fsr

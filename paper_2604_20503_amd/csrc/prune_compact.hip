@@ -34,8 +34,11 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* smem, int& total
     return base + inc - v;
 }
 
+// keep: the mask; or, when accepted_len is given instead, request i keeps its rows 0 .. accepted_len[i]
+// (the survivors of an accept step; always suffix-closed) and keep_out, if not null, receives that mask.
 __global__ __launch_bounds__(kScanThreads) void prune_scan_kernel(
-    const uint8_t* __restrict__ keep, const int32_t* __restrict__ cu_q, int32_t* __restrict__ new_cu_q,
+    const uint8_t* __restrict__ keep, const int32_t* __restrict__ accepted_len, uint8_t* __restrict__ keep_out,
+    const int32_t* __restrict__ cu_q, int32_t* __restrict__ new_cu_q,
     int32_t* __restrict__ new_q_lens, int32_t* __restrict__ src_row, int32_t* __restrict__ dst_row,
     int32_t* __restrict__ n_active, int32_t* __restrict__ active_ids, int B, int N_cap, int suffix_close) {
     __shared__ int smem[kScanThreads / 64 + 1];
@@ -47,7 +50,9 @@ __global__ __launch_bounds__(kScanThreads) void prune_scan_kernel(
         if (i < B) {
             r0 = min(max(cu_q[i], 0), N_cap);  // offsets beyond the allocated rows are cut off
             r1 = min(max(cu_q[i + 1], r0), N_cap);
-            if (suffix_close) {
+            if (accepted_len) {
+                kept = min(max(accepted_len[i] + 1, 0), r1 - r0);
+            } else if (suffix_close) {
                 int r = r0;
                 while (r < r1 && keep[r] != 0) ++r;
                 kept = r - r0;
@@ -65,6 +70,7 @@ __global__ __launch_bounds__(kScanThreads) void prune_scan_kernel(
             int o = off;
             for (int r = r0; r < r1; ++r) {
                 const bool k = suffix_close ? (r - r0 < kept) : (keep[r] != 0);
+                if (keep_out) keep_out[r] = k ? 1 : 0;
                 if (k) {
                     src_row[o] = r;
                     dst_row[r] = o;
@@ -217,21 +223,25 @@ int launch_by_width(size_t row_bytes, const void* a, const void* b, F&& f) {
 
 using namespace fsr;
 
-extern "C" int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, int32_t* new_cu_q,
-                                 int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row, int32_t* n_active,
-                                 int32_t* active_ids, const void* payload_in, void* payload_out, size_t row_bytes,
-                                 const fsr_prune_params* p, void* stream) {
-    if (!p) return fail(FSR_EINVAL, "fsr_prune_compact: params is null");
-    if (p->B < 0 || p->N_cap < 0 || p->reserved != 0) return fail(FSR_EINVAL, "fsr_prune_compact: B=%d N_cap=%d reserved=%d", p->B, p->N_cap, p->reserved);
-    if (!cu_q || !new_cu_q || !n_active) return fail(FSR_EINVAL, "fsr_prune_compact: cu_q/new_cu_q/n_active is null");
-    if (p->B > 0 && (!new_q_lens || !active_ids)) return fail(FSR_EINVAL, "fsr_prune_compact: new_q_lens/active_ids is null");
-    if (p->N_cap > 0 && (!keep_mask || !src_row || !dst_row)) return fail(FSR_EINVAL, "fsr_prune_compact: keep_mask/src_row/dst_row is null");
-    if ((payload_in == nullptr) != (payload_out == nullptr)) return fail(FSR_EINVAL, "fsr_prune_compact: payload_in and payload_out must both be given or both be null");
-    if (payload_in && (row_bytes == 0 || row_bytes % 4 != 0)) return fail(FSR_ESHAPE, "fsr_prune_compact: row_bytes=%zu must be a positive multiple of 4", row_bytes);
-    if (payload_in && payload_in == payload_out) return fail(FSR_EINVAL, "fsr_prune_compact: payload gather cannot run in place");
+namespace {
+// Both compaction entry points: the kept rows come from keep_mask, or from accepted_len (then keep_out, nullable,
+// receives the mask and the rule is suffix-closed by construction).
+int compact_call(const char* who, const uint8_t* keep_mask, const int32_t* accepted_len, uint8_t* keep_out, const int32_t* cu_q,
+                 int32_t* new_cu_q, int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row, int32_t* n_active,
+                 int32_t* active_ids, const void* payload_in, void* payload_out, size_t row_bytes, const fsr_prune_params* p,
+                 void* stream) {
+    if (!p) return fail(FSR_EINVAL, "%s: params is null", who);
+    if (p->B < 0 || p->N_cap < 0 || p->reserved != 0) return fail(FSR_EINVAL, "%s: B=%d N_cap=%d reserved=%d", who, p->B, p->N_cap, p->reserved);
+    if (!cu_q || !new_cu_q || !n_active) return fail(FSR_EINVAL, "%s: cu_q/new_cu_q/n_active is null", who);
+    if (p->B > 0 && (!new_q_lens || !active_ids)) return fail(FSR_EINVAL, "%s: new_q_lens/active_ids is null", who);
+    if (p->N_cap > 0 && ((!keep_mask && !accepted_len) || !src_row || !dst_row))
+        return fail(FSR_EINVAL, "%s: %s/src_row/dst_row is null", who, accepted_len || keep_out ? "accepted_len" : "keep_mask");
+    if ((payload_in == nullptr) != (payload_out == nullptr)) return fail(FSR_EINVAL, "%s: payload_in and payload_out must both be given or both be null", who);
+    if (payload_in && (row_bytes == 0 || row_bytes % 4 != 0)) return fail(FSR_ESHAPE, "%s: row_bytes=%zu must be a positive multiple of 4", who, row_bytes);
+    if (payload_in && payload_in == payload_out) return fail(FSR_EINVAL, "%s: payload gather cannot run in place", who);
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(prune_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, keep_mask, cu_q, new_cu_q, new_q_lens, src_row,
-                       dst_row, n_active, active_ids, p->B, p->N_cap, p->suffix_close);
+    hipLaunchKernelGGL(prune_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, keep_mask, accepted_len, keep_out, cu_q, new_cu_q,
+                       new_q_lens, src_row, dst_row, n_active, active_ids, p->B, p->N_cap, accepted_len ? 1 : p->suffix_close);
     int rc = check_launch("prune_scan_kernel");
     if (rc != FSR_OK) return rc;
     if (payload_in && p->N_cap > 0) {
@@ -246,6 +256,24 @@ extern "C" int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, 
         });
     }
     return rc;
+}
+}  // namespace
+
+extern "C" int fsr_prune_compact(const uint8_t* keep_mask, const int32_t* cu_q, int32_t* new_cu_q,
+                                 int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row, int32_t* n_active,
+                                 int32_t* active_ids, const void* payload_in, void* payload_out, size_t row_bytes,
+                                 const fsr_prune_params* p, void* stream) {
+    return compact_call("fsr_prune_compact", keep_mask, nullptr, nullptr, cu_q, new_cu_q, new_q_lens, src_row, dst_row, n_active,
+                        active_ids, payload_in, payload_out, row_bytes, p, stream);
+}
+
+extern "C" int fsr_survivor_compact(const int32_t* accepted_len, const int32_t* cu_q, uint8_t* keep_mask, int32_t* new_cu_q,
+                                    int32_t* new_q_lens, int32_t* src_row, int32_t* dst_row, int32_t* n_active,
+                                    int32_t* active_ids, const void* payload_in, void* payload_out, size_t row_bytes,
+                                    const fsr_prune_params* p, void* stream) {
+    if (p && p->B > 0 && !accepted_len) return fail(FSR_EINVAL, "fsr_survivor_compact: accepted_len is null");
+    return compact_call("fsr_survivor_compact", nullptr, accepted_len, keep_mask, cu_q, new_cu_q, new_q_lens, src_row, dst_row,
+                        n_active, active_ids, payload_in, payload_out, row_bytes, p, stream);
 }
 
 extern "C" int fsr_prune_restore(const void* compact, const int32_t* dst_row, void* restored, uint8_t* has_value,

@@ -1,6 +1,6 @@
-// Early-exit rank check (Sec. 3.2: a drafted token that falls outside the Top-K set of the
-// intermediate logits becomes a pruning candidate; Sec. 4: the Top-K set is never materialised,
-// it is only checked whether at least K tokens exceed the drafted token's score).
+// Early-exit rank check (Sec. 3.2: intermediate scores predict a rejection when the draft is not
+// among their K best tokens; Sec. 4: decided by counting the scores above the draft's own, without
+// building the set of the K best).
 //
 // The work is one pass over the score row of every draft that still has an active row: count the
 // scores strictly above the draft's own.  That is HBM streaming with a trivial reduction, so the

@@ -9,11 +9,12 @@
 // ~1.3e5, so one workgroup per request cannot fill the chip: every vocabulary row is cut
 // into chunks of kChunk tokens and the vocabulary-wide sums are two-level.
 //   stats    (LOGITS mode only) per (row, chunk): max and sum of exp in fp64
-//   decide   per request, one wave: the sequential accept tests (gathers only), picks the
-//            row pair to sample from and records it
-//   partials per (request, chunk): fp64 mass of the residual and of the target row
-//   select   per request: prefix over the chunk masses -> chunk holding u * R -> scan
-//            inside that chunk -> token
+//   decide   per request, one wave: the accept tests, one lane per draft with all gathers in flight
+//            together; picks the row pair to sample from and records it
+//   sample   grid (chunks, requests): every workgroup sums the fp64 mass of its chunk of the residual
+//            and of the target row; the workgroup of a request that finishes last (found by an arrival
+//            counter that `decide` has zeroed) draws the token: prefix over the chunk masses -> chunk
+//            holding u * R -> scan inside that chunk
 // Only the rows the outcome needs are streamed: one target row (bonus) or one target and
 // one draft row (rejection) per request -- the algorithmic minimum in PROBS mode.
 // All masses are accumulated in fp64 so that the chosen token matches a sequential fp64
@@ -49,6 +50,7 @@ struct Workspace {
     double* mass_tgt;    // [B, n_chunks]
     double* stat_t;      // [R_t_cap, n_chunks, 2]  (LOGITS)
     double* stat_d;      // [R_d_cap, n_chunks, 2]
+    unsigned int* arrivals;  // [B] chunk workgroups of the request that have finished (zeroed by decide)
 };
 
 __host__ __device__ inline int n_chunks_of(int V) { return (V + kChunk - 1) / kChunk; }
@@ -65,6 +67,7 @@ size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
     tmp.dec = (Decision*)take(B * sizeof(Decision));
     tmp.mass_res = (double*)take(B * nc * sizeof(double));
     tmp.mass_tgt = (double*)take(B * nc * sizeof(double));
+    tmp.arrivals = (unsigned int*)take(B * sizeof(unsigned int));
     if (p.mode == FSR_LOGITS) {
         tmp.stat_t = (double*)take(B * (size_t)(p.S_max + 1) * nc * 2 * sizeof(double));
         tmp.stat_d = (double*)take(B * (size_t)p.S_max * nc * 2 * sizeof(double));
@@ -196,76 +199,14 @@ __device__ __forceinline__ void combine_stats(const double* __restrict__ stat, i
     m = mm;
     Z = wave_sum(z);
 }
-
-// ---------------------------------------------------------------------------------------
-// decide: one wave per request runs the accept tests in order.
-// ---------------------------------------------------------------------------------------
-template <int MODE, typename RT>
-__global__ __launch_bounds__(64) void accept_decide_kernel(
-    const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
-    const float* __restrict__ u_accept, const int32_t* __restrict__ cu_t, const int32_t* __restrict__ cu_d,
-    const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows, int32_t* __restrict__ accepted_len,
-    int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
-    const int i = blockIdx.x, lane = threadIdx.x;
-    const int nc = n_chunks_of(V);
-    const int t0 = cu_t[i], t_i = cu_t[i + 1] - t0, d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
-    int32_t* em = emitted + (size_t)i * (S_max + 1);
-    Decision dec;
-    dec.kind = kCaseNone;
-    dec.n = 0;
-    dec.t_row = dec.d_row = 0;
-    dec.m_t = dec.m_d = 0.0;
-    dec.Z_t = dec.Z_d = 1.0;
-    // the per-row statistics hold B*(S_max+1) target and B*S_max draft rows: a call whose offsets
-    // run past that (only possible after an invalid request) is refused for the requests beyond
-    const bool fits = (long long)t0 + t_i <= (long long)B * (S_max + 1) && (long long)d0 + d_i <= (long long)B * S_max;
-    if (d_i < 0 || d_i > S_max || t_i < d_i || t_i > d_i + 1 || t0 < 0 || d0 < 0 || !fits) {
-        for (int s = lane; s <= S_max; s += 64) em[s] = -1;
-        if (lane == 0) {
-            accepted_len[i] = -1;
-            n_emitted[i] = -1;
-            ws.dec[i] = dec;
-        }
-        return;
-    }
-    int n = 0;
-    double m_t = 0.0, Z_t = 1.0, m_d = 0.0, Z_d = 1.0;
-    long long tr = 0, dr = 0;
-    while (n < d_i) {
-        tr = t_rows ? t_rows[t0 + n] : t0 + n;
-        dr = d_rows ? d_rows[d0 + n] : d0 + n;
-        const int x = min(max(draft_tokens[dr], 0), V - 1);
-        const double u = (double)u_accept[dr];
-        if constexpr (MODE == FSR_LOGITS) {
-            combine_stats(ws.stat_t + (size_t)(t0 + n) * nc * 2, nc, m_t, Z_t);
-            combine_stats(ws.stat_d + (size_t)(d0 + n) * nc * 2, nc, m_d, Z_d);
-        }
-        const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t);
-        const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d);
-        if (u * qx < px) {
-            if (lane == 0) em[n] = x;
-            ++n;
-        } else {
-            break;
-        }
-    }
-    dec.n = n;
-    if (n < d_i) {
-        dec.kind = kCaseResidual;
-        dec.t_row = tr;
-        dec.d_row = dr;
-        dec.m_t = m_t; dec.Z_t = Z_t; dec.m_d = m_d; dec.Z_d = Z_d;
-    } else if (t_i == d_i + 1) {
-        dec.kind = kCaseTarget;
-        dec.t_row = t_rows ? t_rows[t0 + d_i] : t0 + d_i;
-        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nc * 2, nc, dec.m_t, dec.Z_t);
-    }
-    for (int s = n + lane; s <= S_max; s += 64) em[s] = -1;
-    if (lane == 0) {
-        accepted_len[i] = n;
-        n_emitted[i] = n;  // select adds the sampled token
-        ws.dec[i] = dec;
-    }
+// The same by one lane on its own (every lane of the wave works on a different row).
+__device__ __forceinline__ void combine_stats_lane(const double* __restrict__ stat, int nc, double& m, double& Z) {
+    double mm = -INFINITY;
+    for (int c = 0; c < nc; ++c) mm = fmax(mm, stat[c * 2]);
+    double z = 0.0;
+    for (int c = 0; c < nc; ++c) z += stat[c * 2 + 1] * exp(stat[c * 2] - mm);
+    m = mm;
+    Z = z;
 }
 
 // Masses of 4 consecutive tokens starting at e for the request's decision.
@@ -291,83 +232,177 @@ __device__ __forceinline__ void quad_masses(const Decision& dec, const RT* __res
     }
 }
 
+__device__ __forceinline__ double shfl_f64(double v, int src) {
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const uint32_t lo = __shfl((uint32_t)b, src, 64), hi = __shfl((uint32_t)(b >> 32), src, 64);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ long long shfl_i64(long long v, int src) {
+    const uint32_t lo = __shfl((uint32_t)v, src, 64), hi = __shfl((uint32_t)((unsigned long long)v >> 32), src, 64);
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+// 8-byte values that another workgroup of the same launch reads: stored through to memory / loaded past the caches
+__device__ __forceinline__ void publish_f64(double* p, double v) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double fetch_f64(const double* p) {
+    return __builtin_bit_cast(double, __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT));
+}
+
 // ---------------------------------------------------------------------------------------
-// partials: fp64 mass of chunk c of request i's sampling distribution.  grid = (n_chunks, B)
+// decide: one wave per request; lane n tests draft n.
 // ---------------------------------------------------------------------------------------
 template <int MODE, typename RT>
-__global__ __launch_bounds__(kThreads) void accept_partials_kernel(const RT* __restrict__ p_target,
-                                                                  const RT* __restrict__ p_draft, Workspace ws,
-                                                                  int V, double T) {
-    __shared__ double smem[kThreads / 64];
-    const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
-    const Decision dec = ws.dec[i];
-    if (dec.kind == kCaseNone) return;
-    const RT* trow = p_target + (size_t)dec.t_row * V;
-    const RT* drow = p_draft + (size_t)dec.d_row * V;
-    const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
-    const int e0 = c * kChunk;
-    double sr = 0.0, st = 0.0;
-#pragma unroll
-    for (int k = 0; k < kPerThread / 4; ++k) {
-        const int e = e0 + (k * kThreads + threadIdx.x) * 4;
-        double res[4], tgt[4];
-        quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
-        sr += (res[0] + res[1]) + (res[2] + res[3]);
-        st += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+__global__ __launch_bounds__(64) void accept_decide_kernel(
+    const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
+    const float* __restrict__ u_accept, const int32_t* __restrict__ cu_t, const int32_t* __restrict__ cu_d,
+    const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows, int32_t* __restrict__ accepted_len,
+    int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int nc = n_chunks_of(V);
+    const int t0 = cu_t[i], t_i = cu_t[i + 1] - t0, d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
+    int32_t* em = emitted + (size_t)i * (S_max + 1);
+    Decision dec;
+    dec.kind = kCaseNone;
+    dec.n = 0;
+    dec.t_row = dec.d_row = 0;
+    dec.m_t = dec.m_d = 0.0;
+    dec.Z_t = dec.Z_d = 1.0;
+    if (lane == 0) ws.arrivals[i] = 0u;
+    // the per-row statistics hold B*(S_max+1) target and B*S_max draft rows: a call whose offsets
+    // run past that (only possible after an invalid request) is refused for the requests beyond
+    const bool fits = (long long)t0 + t_i <= (long long)B * (S_max + 1) && (long long)d0 + d_i <= (long long)B * S_max;
+    if (d_i < 0 || d_i > S_max || t_i < d_i || t_i > d_i + 1 || t0 < 0 || d0 < 0 || !fits) {
+        for (int s = lane; s <= S_max; s += 64) em[s] = -1;
+        if (lane == 0) {
+            accepted_len[i] = -1;
+            n_emitted[i] = -1;
+            ws.dec[i] = dec;
+        }
+        return;
     }
-    sr = block_sum(sr, smem);
-    st = block_sum(st, smem);
-    if (threadIdx.x == 0) {
-        ws.mass_res[(size_t)i * nc + c] = sr;
-        ws.mass_tgt[(size_t)i * nc + c] = st;
+    int n = d_i;  // accepted drafts
+    for (int n0 = 0; n0 < d_i && n == d_i; n0 += 64) {
+        const int k = n0 + lane;
+        const bool live = k < d_i;
+        long long tr = 0, dr = 0;
+        double m_t = 0.0, Z_t = 1.0, m_d = 0.0, Z_d = 1.0;
+        int x = 0;
+        bool ok = true;
+        if (live) {
+            tr = t_rows ? t_rows[t0 + k] : t0 + k;
+            dr = d_rows ? d_rows[d0 + k] : d0 + k;
+            x = min(max(draft_tokens[dr], 0), V - 1);
+            const double u = (double)u_accept[dr];
+            if constexpr (MODE == FSR_LOGITS) {
+                combine_stats_lane(ws.stat_t + (size_t)(t0 + k) * nc * 2, nc, m_t, Z_t);
+                combine_stats_lane(ws.stat_d + (size_t)(d0 + k) * nc * 2, nc, m_d, Z_d);
+            }
+            const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t);
+            const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d);
+            ok = u * qx < px;
+        }
+        const unsigned long long rejected = __builtin_amdgcn_ballot_w64(live && !ok);
+        const int first = rejected ? (int)__builtin_ctzll(rejected) : 64;
+        if (live && lane < first) em[k] = x;  // accepted drafts of this round of 64
+        if (rejected) {
+            n = n0 + first;
+            dec.kind = kCaseResidual;
+            dec.t_row = shfl_i64(tr, first);
+            dec.d_row = shfl_i64(dr, first);
+            dec.m_t = shfl_f64(m_t, first); dec.Z_t = shfl_f64(Z_t, first);
+            dec.m_d = shfl_f64(m_d, first); dec.Z_d = shfl_f64(Z_d, first);
+        }
+    }
+    dec.n = n;
+    if (n == d_i && t_i == d_i + 1) {
+        dec.kind = kCaseTarget;
+        dec.t_row = t_rows ? t_rows[t0 + d_i] : t0 + d_i;
+        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nc * 2, nc, dec.m_t, dec.Z_t);
+    }
+    for (int s = n + lane; s <= S_max; s += 64) em[s] = -1;
+    if (lane == 0) {
+        accepted_len[i] = n;
+        n_emitted[i] = n;  // the sampling kernel adds the drawn token
+        ws.dec[i] = dec;
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// select: inverse CDF.  grid = (B)
+// sample: request i = blockIdx.y; this workgroup owns chunk c = blockIdx.x of the vocabulary.
+// grid = (n_chunks, B)
 // ---------------------------------------------------------------------------------------
 template <int MODE, typename RT>
-__global__ __launch_bounds__(kThreads) void accept_select_kernel(const RT* __restrict__ p_target,
-                                                                const RT* __restrict__ p_draft,
-                                                                const float* __restrict__ u_sample,
-                                                                int32_t* __restrict__ n_emitted,
-                                                                int32_t* __restrict__ emitted, Workspace ws, int V,
-                                                                int S_max, double T) {
+__global__ __launch_bounds__(kThreads) void accept_sample_kernel(
+    const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const float* __restrict__ u_sample,
+    int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int V, int S_max, double T) {
+    __shared__ double smem[kThreads / 64];
     __shared__ double s_wave[kThreads / 64];
     __shared__ int s_i[kThreads / 64];
     __shared__ double s_base, s_thr;
-    __shared__ int s_chunk, s_fallback;
-    const int i = blockIdx.x, nc = n_chunks_of(V);
+    __shared__ int s_chunk, s_fallback, s_last;
+    const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int32_t* em = emitted + (size_t)i * (S_max + 1);
     Decision dec = ws.dec[i];
     if (dec.kind == kCaseNone) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
 
-    // 1. total mass and the chunk that holds u * R (sequential fp64 prefix over <= a few dozen chunks)
+    // ---- 2. fp64 mass of this chunk of the sampling distribution (and of the target row, for the fallback)
+    const RT* trow = p_target + (size_t)dec.t_row * V;
+    const RT* drow = p_draft + (size_t)dec.d_row * V;
+    const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
+    {
+        const int e0 = c * kChunk;
+        double sr = 0.0, st = 0.0;
+#pragma unroll
+        for (int k = 0; k < kPerThread / 4; ++k) {
+            const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+            double res[4], tgt[4];
+            quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
+            sr += (res[0] + res[1]) + (res[2] + res[3]);
+            st += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+        }
+        sr = block_sum(sr, smem);
+        st = block_sum(st, smem);
+        if (threadIdx.x == 0) {
+            publish_f64(ws.mass_res + (size_t)i * nc + c, sr);
+            publish_f64(ws.mass_tgt + (size_t)i * nc + c, st);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // both are in memory before the arrival is counted
+            s_last = atomicAdd(ws.arrivals + i, 1u) == (unsigned)nc - 1u;
+        }
+        __syncthreads();
+        if (!s_last) return;
+    }
+
+    // ---- 3. the request's last workgroup draws the token: total mass and the chunk that holds u * R
+    // (sequential fp64 prefix over <= a few dozen chunks)
     if (threadIdx.x == 0) {
         const double* mres = ws.mass_res + (size_t)i * nc;
         const double* mtgt = ws.mass_tgt + (size_t)i * nc;
         double R = 0.0;
-        for (int c = 0; c < nc; ++c) R += mres[c];
+        for (int cc = 0; cc < nc; ++cc) R += fetch_f64(mres + cc);
         int fallback = 0;
         const double* mass = mres;
         if (!(R > 0.0)) {  // residual is all zero: sample from the target row itself
             fallback = 1;
             mass = mtgt;
             R = 0.0;
-            for (int c = 0; c < nc; ++c) R += mtgt[c];
+            for (int cc = 0; cc < nc; ++cc) R += fetch_f64(mtgt + cc);
         }
         const double thr = (double)u_sample[i] * R;
         double acc = 0.0, base = 0.0;
         int chunk = -1, last_pos = 0;
         double last_base = 0.0;
-        for (int c = 0; c < nc; ++c) {
-            const double prev = acc;
-            acc += mass[c];
-            if (mass[c] > 0.0) {
-                last_pos = c;
+        for (int cc = 0; cc < nc; ++cc) {
+            const double prev = acc, mc = fetch_f64(mass + cc);
+            acc += mc;
+            if (mc > 0.0) {
+                last_pos = cc;
                 last_base = prev;
                 if (acc > thr) {
-                    chunk = c;
+                    chunk = cc;
                     base = prev;
                     break;
                 }
@@ -385,13 +420,10 @@ __global__ __launch_bounds__(kThreads) void accept_select_kernel(const RT* __res
     __syncthreads();
     if (s_fallback) dec.kind = kCaseTarget;
     const double thr = s_thr;
-    const int c = s_chunk;
+    const int cs = s_chunk;
 
-    // 2. scan inside the chunk: thread t owns tokens [16 t, 16 t + 16) of the chunk
-    const RT* trow = p_target + (size_t)dec.t_row * V;
-    const RT* drow = p_draft + (size_t)dec.d_row * V;
-    const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
-    const int e0 = c * kChunk + threadIdx.x * kPerThread;
+    // scan inside the chunk: thread t owns tokens [16 t, 16 t + 16) of the chunk
+    const int e0 = cs * kChunk + threadIdx.x * kPerThread;
     double mass[kPerThread];
     double local = 0.0;
 #pragma unroll
@@ -431,7 +463,7 @@ __global__ __launch_bounds__(kThreads) void accept_select_kernel(const RT* __res
     if (threadIdx.x == 0) {
         int tok = hit != INT_MAX ? hit : last_pos;
         if (tok < 0) tok = 0;  // unreachable for a chunk with mass; keeps the id in range
-        emitted[(size_t)i * (S_max + 1) + dec.n] = tok;
+        em[dec.n] = tok;
         n_emitted[i] = dec.n + 1;
     }
 }
@@ -453,11 +485,9 @@ int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_token
     hipLaunchKernelGGL((accept_decide_kernel<MODE, RT>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
                        cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T);
     if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
-    hipLaunchKernelGGL((accept_partials_kernel<MODE, RT>), dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, ws, p.V, T);
-    if ((rc = check_launch("accept_partials_kernel")) != FSR_OK) return rc;
-    hipLaunchKernelGGL((accept_select_kernel<MODE, RT>), dim3(p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
+    hipLaunchKernelGGL((accept_sample_kernel<MODE, RT>), dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
                        emitted, ws, p.V, p.S_max, T);
-    return check_launch("accept_select_kernel");
+    return check_launch("accept_sample_kernel");
 }
 
 int validate(const fsr_accept_params* p, const char* who) {

@@ -26,7 +26,10 @@
 //     -- and the workgroup whose piece arrives last combines them, in the same launch.
 // Generic path (fp32 or bf16, D in {64,128}, any page size): one wave per (row, head), plain
 // fp32 FMAs -- a correctness path for small or unusual shapes, not a bandwidth kernel.
+#include <algorithm>
 #include <atomic>
+#include <map>
+#include <mutex>
 
 #include "common.hpp"
 #include "device_utils.hpp"
@@ -54,8 +57,8 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kMaxMT = 4;         // up to 64 query rows (G * suffix positions) per row group
 constexpr int kMaxB = 4096;       // requests whose tile prefix fits the LDS table
 constexpr int kRedStride = kD + 4;  // padded row of the wave-merge buffer (floats)
-// LDS map: [V tiles of the 4 waves | wave-merge buffer] (shared region), wave maxima and sums,
-// Q^T operands, tile prefix of the requests, scan scratch
+// LDS map, fixed part: [V tiles of the 4 waves | wave-merge buffer] (shared region), wave maxima and
+// sums, Q^T operands
 constexpr int kVTileBytes = kTile * kD * 2;
 constexpr int kRedBytes = kWaves * 16 * kRedStride * 4;
 constexpr int kStageBytes = kWaves * kVTileBytes > kRedBytes ? kWaves * kVTileBytes : kRedBytes;
@@ -63,13 +66,15 @@ constexpr int kMlOff = kStageBytes;
 constexpr int kMlBytes = 2 * kWaves * 16 * kMaxMT * 4;
 constexpr int kQOff = kMlOff + kMlBytes;          // Q^T operands of the current item: [kMaxMT * 4][64 lanes][16 B]
 constexpr int kQBytes = kMaxMT * 4 * 64 * 16;
-constexpr int kPrefOff = kQOff + kQBytes;
-constexpr int kPrefBytes = (kMaxB + 1) * 8;          // weighted tile prefix (64-bit)
-constexpr int kScanOff = kPrefOff + ((kPrefBytes + 15) / 16) * 16;
-// copies of the row offsets and context lengths the prefix has loaded anyway: the walker reads them here
-constexpr int kCuOff = kScanOff + 64;
-constexpr int kCtxOff = kCuOff + (kMaxB + 4) * 4;
-constexpr int kFastSmem = kCtxOff + kMaxB * 4;
+// Behind the fixed part, the kernel that builds its own schedule keeps three tables sized from the
+// call's B: weighted tile prefix (64-bit, B + 1 entries), scan scratch, and copies of the row offsets
+// and context lengths the prefix has loaded anyway (the walker reads them there).
+constexpr int kFixedSmem = kQOff + kQBytes;
+__host__ __device__ constexpr int pref_off() { return kFixedSmem; }
+__host__ __device__ constexpr int scan_off(int B) { return pref_off() + ((B + 1) * 8 + 15) / 16 * 16; }
+__host__ __device__ constexpr int cu_off(int B) { return scan_off(B) + 64; }
+__host__ __device__ constexpr int ctx_off(int B) { return cu_off(B) + (B + 4) * 4; }
+__host__ __device__ constexpr int sched_smem(int B) { return ctx_off(B) + (B + 4) * 4; }
 // Measured: a tile takes 2.0 / 2.4 / 2.5 us per wave with 1 / 2 / 3 query tiles riding on it (bandwidth, not the
 // matrix work, sets the pace), and taking up an item costs a workgroup 6 to 10 us of merge, count and refill.
 // Swept on four batches of the 16-request shape and on the 128- and 512-request shapes: base 3..6 with 12..20
@@ -93,10 +98,12 @@ struct FastArgs {
     const int32_t* cu_q;
     void* out;       // [N_cap, H_q, D] bf16 or fp32
     float* lse;      // nullable
-    float* part_o;   // [nb * 2, m_cap, D]   unnormalised accumulators of cut items
-    float* part_ml;  // [nb * 2, m_cap, 2]   (exponent reference in log2 units, sum)
-    unsigned long long* arrivals;  // [nb] (call id << 16 | pieces of a cut item that have arrived)
-    unsigned long long call_id;    // distinguishes this call's counts from whatever the words held before
+    float* part_o;   // [shares * 2, m_cap, D]   unnormalised accumulators of cut items
+    float* part_ml;  // [shares * 2, m_cap, 4]   (exponent reference in log2 units, sum, call tag, unused)
+    unsigned long long* arrivals;  // [shares + 1] (call id << 16 | pieces of a cut item that have arrived)
+    unsigned long long call_id;    // distinguishes this call's counts and partials from whatever the workspace held before
+    const int32_t* plan;           // schedule written by attn_plan_kernel (planned kernel only)
+    uint32_t plan_key;             // what the plan must have been built for (planned kernel only)
     int B, H_q, H_kv, G, max_pages, n_pages;
     int nb;          // workgroups of the persistent grid
     int m_cap;       // rows (G * q_len) a partial slot holds = 16 * MTMAX
@@ -106,28 +113,19 @@ struct FastArgs {
     const float* v_scale;  // the same for values
     int cost_base;   // fixed part of a tile's cost (see tile_cost)
     int seg_tiles;   // phantom tiles in front of every item on the cost line (see the schedule)
-#ifdef FSR_TIMING
-    long long* dbg;  // [nb][128 slots][4 waves] timestamps (100 MHz)
-#endif
 };
 
-#ifdef FSR_TIMING
-#define FSR_STAMP(slot) do { if ((threadIdx.x & 63) == 0) { const int w_ = threadIdx.x >> 6; a.dbg[(size_t)blockIdx.x * 512 + (slot) * 4 + w_] = wall_clock64(); } } while (0)
-#else
-#define FSR_STAMP(slot) do { } while (0)
-#endif
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-// Accesses that go to the device's point of coherence (past the per-die L2), for the few KB that
-// workgroups hand to each other inside one launch.  64-bit relaxed device-scope atomics: the widest
-// form the compiler offers, and it can keep many of them in flight before it waits.
-__device__ __forceinline__ void coherent_store2(float* p, float x, float y) {
-    const unsigned long long bits = (unsigned long long)__builtin_bit_cast(uint32_t, x) | ((unsigned long long)__builtin_bit_cast(uint32_t, y) << 32);
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Stores that go to the device's point of coherence (past the per-die L2), for the few KB that
+// workgroups hand to each other inside one launch: 16-byte buffer stores with the device-scope bit, so a
+// wave's store instruction covers whole cache lines (narrower ones reach memory as partial-line writes).
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+constexpr int kStoreDeviceScope = 16;  // cache-policy bit "sc1" of the buffer store
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_buffer(float* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7fffffff, 0x00020000);
 }
-__device__ __forceinline__ void coherent_store4(float* p, f32x4 v) {
-    coherent_store2(p, v[0], v[1]);
-    coherent_store2(p + 2, v[2], v[3]);
+__device__ __forceinline__ void coherent_store4(__amdgpu_buffer_rsrc_t buf, size_t float_index, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), buf, (int)(float_index * 4), 0, kStoreDeviceScope);
 }
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
@@ -265,12 +263,17 @@ __device__ __forceinline__ void e4m3x16_to_bf16(u32x4 w, u32x4& first8, u32x4& n
 struct Segment {
     int i, kvh, c, q0, q_len, j0, rows_g, tile_a, tile_e, slot;
     bool final_out;
+    // an item cut by share boundaries: its pieces are the shares b_first .. b_last
+    bool cut;
+    int b_first, b_last;
 };
 
 // One wave's view of a segment's K/V tiles: keys kb0 + t * (kWaves * kTile), t = 0 .. nw-1.
 struct KVStream {
     const const_i32* bt;  // the request's block table, read through the constant address space so
                           // that the (wave-uniform) page look-ups are scalar loads
+    const const_i32* bt_first;  // where the pages of the wave's first two tiles are looked up: the block
+                                // table again, or the copy of those entries that a plan record carries
     gmem_char* k_head;   // caches offset to the KV head
     gmem_char* v_head;
     int kb0, nw, kv_total, kend;
@@ -318,6 +321,7 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     KVStream st;
     st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
+    st.bt_first = st.bt;
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
     st.k_head = (gmem_char*)a.k + (size_t)kvh * head_stride<TM, KV8>();
     st.v_head = (gmem_char*)a.v + (size_t)kvh * head_stride<TM, KV8>();
@@ -332,22 +336,31 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     return st;
 }
 
-// Issue the global loads of the wave's tile ti (no waiting).  Tiles past the wave's last one are
-// "issued" too, so that the number of loads in flight is the same on every path and the compiler's
-// wait counts stay exact: all their lanes read the first bytes of the last tile (16 cache lines,
-// already resident) and nothing consumes them.  Needs st.nw > 0.
-// Walks a workgroup's share [x, x1) of the cost line and hands out its segments in order.
+// Shares and workgroups.  The hardware hands consecutive workgroups of a grid to the dies (XCDs) in
+// turn, so workgroup w runs on die w % kDies.  Share ids are assigned die by die: the workgroups of
+// one die hold consecutive shares, and the pieces of an item cut by share boundaries nearly always
+// sit behind one L2 (only the seven boundaries between dies separate neighbours).  Nothing depends
+// on the hardware keeping to that order: the exchange below is correct across dies as well.
+constexpr int kDies = 8;
+__device__ __forceinline__ int share_of_block(int w, int n) {  // w < n workgroups take part
+    const int die = w % kDies, idx = w / kDies;
+    // workgroups w' < n with w' % kDies < die
+    const int full = n / kDies, extra = n % kDies;
+    return die * full + min(die, extra) + idx;
+}
+
+// Walks a share [x, x1) of the cost line and hands out its segments in order.  UNI: the walker runs
+// in all lanes of a wave alike (the attention kernel), so what it looks up is moved to scalar
+// registers; the plan kernel walks a different share in every lane.
+template <bool UNI>
 struct ShareWalker {
     const long long* pref;
     const int* lds_cu;   // LDS copies of cu_q (B + 1 entries) and of max(ctx_lens, 0)
     const int* lds_ctx;
     long long x, x1, T, q;
     int nb, r, b, mt_max;
-    // what the segment just handed out is part of (for counting the pieces of a cut item)
-    long long first_end, item_end;  // cost position where the item's first real tile ends / the item ends
-    int item_rows;
-    bool cut;
 
+    static __device__ __forceinline__ int uni(int v) { return UNI ? uniform(v) : v; }
     // nb shares of q or q + 1 units (the first r are the longer ones)
     __device__ void set_shares(long long total, int n) {
         T = total; nb = n;
@@ -365,8 +378,8 @@ struct ShareWalker {
         while (x < x1) {
             // scalar loads (constant address space, uniform index): they must not queue behind the K/V
             // tile loads that are in flight while the next segment is being looked up
-            const int ri = uniform(locate_request(pref, a.B, a.H_kv, x));
-            const int q0 = uniform(lds_cu[ri]), q_len = uniform(lds_cu[ri + 1]) - q0, c = uniform(lds_ctx[ri]);
+            const int ri = uni(locate_request(pref, a.B, a.H_kv, x));
+            const int q0 = uni(lds_cu[ri]), q_len = uni(lds_cu[ri + 1]) - q0, c = uni(lds_ctx[ri]);
             // the KV head, then the row group, that hold position x
             const long long per_head = pref[ri + 1] - pref[ri], req_base = pref[ri] * a.H_kv;
             const int g = (int)div_u(x - req_base, per_head);
@@ -377,18 +390,24 @@ struct ShareWalker {
                 gr = group_at(a, mt_max, c, q_len, gr.j0 + gr.rows_g);
             }
             const long long iend = base + (long long)gr.nt * gr.cost;
-            // tiles [xt_a, xt_e) of the item, phantom tiles included, are this workgroup's
+            // tiles [xt_a, xt_e) of the item, phantom tiles included, are this share's
             const int xt_a = (int)div_u(x - base, gr.cost);
             const int xt_e = x1 >= iend ? gr.nt : (int)div_u(x1 - base, gr.cost);
             const int nt = gr.nt - a.seg_tiles, tile_a = max(xt_a - a.seg_tiles, 0), tile_e = max(xt_e - a.seg_tiles, 0);
             x = x1 >= iend ? iend : x1;
             if (tile_e > tile_a) {
-                sg.i = ri; sg.kvh = uniform(g); sg.c = c; sg.q0 = q0; sg.q_len = q_len;
+                sg.i = ri; sg.kvh = uni(g); sg.c = c; sg.q0 = q0; sg.q_len = q_len;
                 sg.j0 = gr.j0; sg.rows_g = gr.rows_g; sg.tile_a = tile_a; sg.tile_e = tile_e;
                 sg.final_out = tile_a == 0 && tile_e == nt;
                 sg.slot = b * 2 + (tile_a > 0 ? 0 : 1);
-                first_end = base + (long long)(a.seg_tiles + 1) * gr.cost; item_end = iend; item_rows = a.G * gr.rows_g;
-                cut = !sg.final_out;
+                sg.cut = !sg.final_out;
+                sg.b_first = sg.b_last = b;
+                if (sg.cut) {
+                    // pieces of this item: the shares that own its first .. last tile; share bb owns
+                    // tile k iff share_start(bb) < base + (k + 1) * cost <= share_start(bb + 1)
+                    sg.b_first = owner_of(base + (long long)(a.seg_tiles + 1) * gr.cost);
+                    sg.b_last = owner_of(iend);
+                }
                 return true;
             }
         }
@@ -396,11 +415,17 @@ struct ShareWalker {
     }
 };
 
+// Issue the global loads of the wave's tile ti (no waiting); bt = the table in which the tile's pages
+// are looked up.  Tiles past the wave's last one are "issued" too, so that the number of loads in
+// flight is the same on every path and the compiler's wait counts stay exact: all their lanes read
+// the first bytes of the last tile (16 cache lines, already resident) and nothing consumes them.
+// Needs st.nw > 0.
 template <bool TM, bool KV8>
-__device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, typename TileOf<KV8>::type& t, int ti) {
+__device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, const const_i32* bt, typename TileOf<KV8>::type& t,
+                                           int ti) {
     const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
     KVStream st;
-    st.bt = uniform(sv.bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
+    st.bt = uniform(bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
     st.kb0 = uniform(sv.kb0); st.nw = uniform(sv.nw); st.kv_total = uniform(sv.kv_total);
     ti = uniform(ti);
     const bool real = ti < st.nw;
@@ -449,8 +474,7 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
 
 // Process one segment: stream the wave's tiles, merge the 4 waves, write the result or the partial.
 template <int MT, bool TM, bool KV8>
-__device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem, int seg_no) {
-    FSR_STAMP(seg_no * 5 + 2);
+__device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem) {
     // everything that is the same for the whole wave goes to scalar registers
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
     const int c = __builtin_amdgcn_readfirstlane(sg.c);
@@ -477,7 +501,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         for (int db = 0; db < 8; ++db) vr_off[db] = vtile_off(r0, 2 * db + ((li & 3) >> 1)) + (li & 1) * 8;
     }
     typedef typename TileOf<KV8>::type Tile;
-    auto issue = [&](Tile& t, int ti) { issue_tile<TM, KV8>(a, st, t, ti); };
+    auto issue = [&](Tile& t, int ti) { issue_tile<TM, KV8>(a, st, st.bt, t, ti); };
     // with 8-bit caches the per-head key scale joins the softmax scale and the value scale the merge
     const float sl2 = KV8 ? a.scale_log2 * a.k_scale[kvh] : a.scale_log2;
     const float v_mul = KV8 ? a.v_scale[kvh] : 1.0f;
@@ -492,8 +516,8 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     constexpr int kDepth = 2;
     Tile ta, tb;
     if (nw > 0) {
-        issue(ta, 0);
-        issue(tb, 1);
+        issue_tile<TM, KV8>(a, st, st.bt_first, ta, 0);
+        issue_tile<TM, KV8>(a, st, st.bt_first, tb, 1);
     }
 
     // ---- Q^T operands: lane holds query row (mt*16 + li), d = 32 kk + 8 lg .. +7.  They are the
@@ -521,7 +545,6 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
     __syncthreads();
 
-    FSR_STAMP(seg_no * 5 + 3);
     float m_run[MT], l_run[MT];
     f32x4 acc[MT][8];
     auto reset_state = [&]() {
@@ -711,9 +734,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             __builtin_amdgcn_sched_barrier(0);
             issue(tl, t + kDepth);
             __builtin_amdgcn_sched_barrier(0);
-            if (seg_no == 0 && t < 24) FSR_STAMP(16 + 2 * t);
             if (real) fast_softmax_pv(kb0 + t * kStep, s);
-            if (seg_no == 0 && t < 24) FSR_STAMP(17 + 2 * t);
         };
         for (int t = 0; t < nw; t += kDepth) {
             fast_tile(ta, t);
@@ -786,7 +807,6 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         }
     }
 
-    FSR_STAMP(seg_no * 5 + 4);
     // ---- row sums live spread over the 4 lane groups
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -798,6 +818,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     float* red_m = reinterpret_cast<float*>(smem + kMlOff);   // [kWaves][96]
     float* red_l = red_m + kWaves * 16 * kMaxMT;
     float* red_o = reinterpret_cast<float*>(smem);            // [kWaves][16][kRedStride], shares the V tiles' space
+    const __amdgpu_buffer_rsrc_t buf_o = partial_buffer(a.part_o), buf_ml = partial_buffer(a.part_ml);
     __syncthreads();
     if (lg == 0) {
 #pragma unroll
@@ -862,13 +883,10 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
                 } else {
                     // pieces are read by another workgroup of this launch, possibly on another die:
                     // device-coherent stores (written through to memory) instead of a cache flush before the count
-                    float* dst = a.part_o + ((size_t)slot * a.m_cap + m) * kD + d0;
-                    coherent_store4(dst, s0);
-                    coherent_store4(dst + 4, s1);
-                    if (d0 == 0) {
-                        float* ml = a.part_ml + ((size_t)slot * a.m_cap + m) * 2;
-                        coherent_store2(ml, ms, ls);
-                    }
+                    const size_t prow = (size_t)slot * a.m_cap + m;
+                    coherent_store4(buf_o, prow * kD + d0, s0);
+                    coherent_store4(buf_o, prow * kD + d0 + 4, s1);
+                    if (d0 == 0) coherent_store4(buf_ml, prow * 4, f32x4{ms, ls, __builtin_bit_cast(float, (uint32_t)a.call_id), 0.0f});
                 }
             }
         }
@@ -877,10 +895,9 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
 }
 
 template <int MTMAX, bool TM, bool KV8>
-__device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem,
-                                                int seg_no) {
+__device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem) {
     const int mt = (a.G * sg.rows_g + 15) >> 4;
-#define FSR_SEG(MT) attend_segment<MT, TM, KV8>(a, sg, st, smem, seg_no)
+#define FSR_SEG(MT) attend_segment<MT, TM, KV8>(a, sg, st, smem)
     if constexpr (MTMAX == 1) {
         FSR_SEG(1);
     } else if constexpr (MTMAX == 2) {
@@ -928,9 +945,12 @@ __device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int
                 // read once per launch, so neither this compute unit's L1 nor this die's L2 can hold an older copy
                 // of it from this launch, and copies from earlier launches are dropped when a kernel starts (the same
                 // rule that lets any kernel read what an earlier kernel wrote on another die).
-                const float2 ml2 = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
-                pm[e][k] = ml2.x;
-                pl[e][k] = ml2.y;
+                const f32x4 ml4 = *reinterpret_cast<const f32x4*>(a.part_ml + row * 4);
+                // a slot that this call did not write (a workspace shared by overlapping calls) poisons the row
+                // instead of being summed silently
+                const float ref = ml4[0], sum = ml4[1], tag = ml4[2];
+                pm[e][k] = __builtin_bit_cast(uint32_t, tag) == (uint32_t)a.call_id ? ref : __builtin_nanf("");
+                pl[e][k] = sum;
                 po[e][k] = *reinterpret_cast<const f32x4*>(a.part_o + row * kD + d0);
             }
         }
@@ -975,83 +995,196 @@ __device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int
     }
 }
 
-// One more piece of a cut item is in memory: count it.  The word holds (call id << 16 | count); a
-// word left by another call (or never written) counts as zero, so the workspace needs no clearing.
-__device__ __forceinline__ int count_arrival(unsigned long long* word, unsigned long long call_id) {
-    unsigned long long seen = __atomic_load_n(word, __ATOMIC_RELAXED);
-    for (;;) {
-        const unsigned long long have = (seen >> 16) == call_id ? (seen & 0xffffu) : 0u;
-        const unsigned long long want = (call_id << 16) | (have + 1);
-        const unsigned long long prev = atomicCAS(word, seen, want);
-        if (prev == seen) return (int)(have + 1);
-        seen = prev;
+// After a segment that is a piece of a cut item: count the piece; the workgroup whose piece arrives
+// last combines them all.  Called by the whole workgroup.
+template <int MTMAX>
+__device__ __forceinline__ void finish_piece(const FastArgs& a, const Segment& sg, int* s_last) {
+    // the piece's stores are device-coherent; once every wave has seen them acknowledged the piece
+    // may be counted
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) *s_last = count_arrival(a.arrivals + sg.b_first + 1, a.call_id) == sg.b_last - sg.b_first + 1;
+    __syncthreads();
+    if (*s_last) {
+        combine_cut_item<MTMAX>(a, sg.b_first, sg.b_last, sg.kvh, sg.q0 + sg.j0, a.G * sg.rows_g);
+        if (threadIdx.x == 0) __atomic_store_n(a.arrivals + sg.b_first + 1, a.call_id << 16, __ATOMIC_RELAXED);
     }
+    __syncthreads();
 }
 
 // Persistent grid: nb workgroups of 256 threads; the cost line [0, T) is cut into nb' = min(nb,
-// T / dearest tile) shares whose lengths differ by at most one unit, workgroup b takes share b.  A
-// workgroup owns the tiles that END inside its share (phantom tiles are owned and skipped).  An item that lies
+// T / dearest tile) shares whose lengths differ by at most one unit, every workgroup takes one share.  A
+// share owns the tiles that END inside it (phantom tiles are owned and skipped).  An item that lies
 // inside one share is finished by that workgroup; an item cut by share boundaries leaves one
 // partial per piece, and the workgroup whose piece arrives last combines them (no workgroup ever
 // waits for another).
+//
+// attn_stream_kernel builds the schedule itself, from the lengths, at the start of every launch.
 template <int MTMAX, bool TM, bool KV8>
 __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
-    long long* pref = reinterpret_cast<long long*>(smem + kPrefOff);
-    FSR_STAMP(0);
-#ifdef FSR_TIMING
-    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 126 * 4] = clock64();
-#endif
-    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + kScanOff),
-                                       reinterpret_cast<int*>(smem + kCuOff), reinterpret_cast<int*>(smem + kCtxOff));
-    FSR_STAMP(1);
-    ShareWalker wk;
+    long long* pref = reinterpret_cast<long long*>(smem + pref_off());
+    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + scan_off(a.B)),
+                                       reinterpret_cast<int*>(smem + cu_off(a.B)), reinterpret_cast<int*>(smem + ctx_off(a.B)));
+    ShareWalker<true> wk;
     wk.pref = pref;
-    wk.lds_cu = reinterpret_cast<const int*>(smem + kCuOff);
-    wk.lds_ctx = reinterpret_cast<const int*>(smem + kCtxOff);
-    {
-        // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
-        // item then owns at least one of its tiles
-        const long long total = pref[a.B] * a.H_kv;
-        const int nbx = (int)min((long long)a.nb, div_u(total, cmax));
-        if ((int)blockIdx.x >= nbx) return;
-        wk.set_shares(total, nbx);
-    }
-    wk.b = blockIdx.x; wk.mt_max = MTMAX; wk.cut = false;
-    if (wk.b >= wk.nb) return;
+    wk.lds_cu = reinterpret_cast<const int*>(smem + cu_off(a.B));
+    wk.lds_ctx = reinterpret_cast<const int*>(smem + ctx_off(a.B));
+    // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
+    // item then owns at least one of its tiles
+    const long long total = pref[a.B] * a.H_kv;
+    const int nbx = (int)min((long long)a.nb, div_u(total, cmax));
+    wk.b = share_of_block(blockIdx.x, a.nb);
+    if (wk.b >= nbx) return;
+    wk.set_shares(total, nbx);
+    wk.mt_max = MTMAX;
     wk.x = wk.share_start(wk.b);
     wk.x1 = wk.share_start(wk.b + 1);
 
     Segment cur;
-    int seg_no = 0;
     while (wk.next(a, cur)) {
         const KVStream st = make_stream<TM, KV8>(a, cur);
-        attend_dispatch<MTMAX, TM, KV8>(a, cur, st, smem, min(seg_no, 2));
-        ++seg_no;
-        if (wk.cut) {
-            // pieces of this item: the workgroups that own its first .. last tile; workgroup bb owns
-            // tile k iff share_start(bb) < base + (k + 1) * cost <= share_start(bb + 1)
-            const int b_first = wk.owner_of(wk.first_end), b_last = wk.owner_of(wk.item_end);
-            // the piece's stores are device-coherent; once every wave has seen them acknowledged the
-            // piece may be counted
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (threadIdx.x == 0) s_last = count_arrival(a.arrivals + b_first + 1, a.call_id) == b_last - b_first + 1;
-            __syncthreads();
-            FSR_STAMP(100 + min(seg_no - 1, 1) * 2);
-            if (s_last) {
-                combine_cut_item<MTMAX>(a, b_first, b_last, cur.kvh, cur.q0 + cur.j0, wk.item_rows);
-                if (threadIdx.x == 0) __atomic_store_n(a.arrivals + b_first + 1, a.call_id << 16, __ATOMIC_RELAXED);
+        attend_dispatch<MTMAX, TM, KV8>(a, cur, st, smem);
+        if (cur.cut) finish_piece<MTMAX>(a, cur, &s_last);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Planned schedule.  Lengths, row offsets and block tables are the same for every layer of a
+// verification step, so the schedule can be built once per step (attn_plan_kernel) and the
+// per-layer launches (attn_planned_kernel) then start their first K/V loads one scalar-load round
+// trip after they begin: a workgroup reads the record of its first segment, which also carries the
+// page ids of the first two tiles of each of its waves.
+//
+// Plan buffer (int32 words): header record, then one record per share (its first segment), then the
+// further segments of all shares, share after share.  A record is kRecInts words:
+//   0 request  1 KV head  2 context  3 first row  4 rows of the request  5 first suffix position of
+//   the row group  6 positions in the group  7,8 tile range  9 flags (1 = whole item, 2 = cut)
+//   10,11 first / last share of the cut item  12 partial slot  13 segments of this share (first
+//   record only)  14 index of the share's second segment among the further ones (first record only)
+//   16..31 page ids of the item's tiles tile_a .. tile_a + 7 (two pages each, clamped to the pool and
+//   to the request's last page)
+// Header: 0 magic, 1 key of the shapes the plan was built for, 2 shares in use.
+// ---------------------------------------------------------------------------------------
+constexpr int kRecInts = 32;
+constexpr int kMaxShares = 1024;  // the workspace and the plan are laid out for up to this many workgroups
+constexpr int32_t kPlanMagic = 0x46535250;
+
+__device__ __forceinline__ void write_record(int32_t* rec, const FastArgs& a, const Segment& sg, int n_seg, int more_at) {
+    int32_t w[kRecInts];
+    w[0] = sg.i; w[1] = sg.kvh; w[2] = sg.c; w[3] = sg.q0; w[4] = sg.q_len; w[5] = sg.j0; w[6] = sg.rows_g;
+    w[7] = sg.tile_a; w[8] = sg.tile_e; w[9] = (sg.final_out ? 1 : 0) | (sg.cut ? 2 : 0);
+    w[10] = sg.b_first; w[11] = sg.b_last; w[12] = sg.slot; w[13] = n_seg; w[14] = more_at; w[15] = 0;
+    const int kv_total = min(sg.c + sg.q_len, a.max_pages * kP);
+    const int last_page = max((kv_total + kP - 1) / kP - 1, 0);
+    const int32_t* bt = a.bt + (size_t)sg.i * a.max_pages;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) w[16 + k] = min(max(bt[min(2 * sg.tile_a + k, last_page)], 0), a.n_pages - 1);
+#pragma unroll
+    for (int k = 0; k < kRecInts; k += 4) *reinterpret_cast<int4*>(rec + k) = make_int4(w[k], w[k + 1], w[k + 2], w[k + 3]);
+}
+
+// One workgroup; thread t walks shares t, t + 256, ... twice (count, then write).
+__global__ __launch_bounds__(kThreads) void attn_plan_kernel(FastArgs a, int mt_max, int32_t* plan, int more_cap) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    long long* pref = reinterpret_cast<long long*>(smem + pref_off());
+    long long* scratch = reinterpret_cast<long long*>(smem + scan_off(a.B));
+    int* cnt = reinterpret_cast<int*>(smem + sched_smem(a.B));  // [kMaxShares] segments of a share, then where its further ones start
+    const int cmax = build_cost_prefix(a, mt_max, pref, scratch, reinterpret_cast<int*>(smem + cu_off(a.B)),
+                                       reinterpret_cast<int*>(smem + ctx_off(a.B)));
+    ShareWalker<false> wk;
+    wk.pref = pref;
+    wk.lds_cu = reinterpret_cast<const int*>(smem + cu_off(a.B));
+    wk.lds_ctx = reinterpret_cast<const int*>(smem + ctx_off(a.B));
+    wk.mt_max = mt_max;
+    const long long total = pref[a.B] * a.H_kv;
+    const int nbx = (int)min((long long)a.nb, div_u(total, cmax));
+    if (nbx > 0) wk.set_shares(total, nbx);
+    for (int s = threadIdx.x; s < kMaxShares; s += kThreads) {
+        int n = 0;
+        if (s < nbx) {
+            wk.b = s; wk.x = wk.share_start(s); wk.x1 = wk.share_start(s + 1);
+            Segment sg;
+            while (wk.next(a, sg)) ++n;
+        }
+        cnt[s] = n;
+    }
+    __syncthreads();
+    // exclusive scan of max(cnt - 1, 0): thread t owns shares 4 t .. 4 t + 3
+    {
+        const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+        int mine[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            mine[j] = sum;
+            sum += max(cnt[4 * threadIdx.x + j] - 1, 0);
+        }
+        const int inc = wave_inclusive_scan(sum);
+        __syncthreads();  // every count has been read; the table is reused for the offsets
+        if (lane == 63) scratch[w] = inc;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k)
+            if (k < w) before += (int)scratch[k];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cnt[4 * threadIdx.x + j] = before + inc - sum + mine[j];
+        __syncthreads();
+    }
+    int32_t* first = plan + kRecInts;
+    int32_t* more = first + (size_t)kMaxShares * kRecInts;
+    for (int s = threadIdx.x; s < a.nb; s += kThreads) {
+        const int more_at = cnt[s];
+        int n = 0;
+        Segment sg, head;
+        if (s < nbx) {
+            wk.b = s; wk.x = wk.share_start(s); wk.x1 = wk.share_start(s + 1);
+            while (wk.next(a, sg)) {
+                if (n == 0) head = sg;
+                else if (more_at + n - 1 < more_cap) write_record(more + (size_t)(more_at + n - 1) * kRecInts, a, sg, 0, 0);
+                else break;  // cannot happen with the capacity the host computes; stay inside the buffer anyway
+                ++n;
             }
-            __syncthreads();
-            FSR_STAMP(101 + min(seg_no - 1, 1) * 2);
+        }
+        if (n > 0) {
+            write_record(first + (size_t)s * kRecInts, a, head, n, more_at);
+        } else {
+            first[(size_t)s * kRecInts + 13] = 0;
         }
     }
-    FSR_STAMP(15);
-#ifdef FSR_TIMING
-    if (threadIdx.x == 0) a.dbg[(size_t)blockIdx.x * 512 + 127 * 4] = clock64();
-#endif
+    if (threadIdx.x == 0) {
+        plan[2] = nbx;
+        plan[1] = (int32_t)a.plan_key;
+        plan[0] = kPlanMagic;
+    }
+}
+
+template <int MTMAX, bool TM, bool KV8>
+__global__ __launch_bounds__(kThreads) void attn_planned_kernel(FastArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_last;
+    const const_i32* plan = (const const_i32*)a.plan;
+    const int share = share_of_block(blockIdx.x, a.nb);
+    const const_i32* rec = plan + (size_t)(1 + share) * kRecInts;
+    // a buffer that holds no plan, or one built for other shapes, is left alone (the host checks the
+    // shapes before the launch; this guards the memory accesses below)
+    if (plan[0] != kPlanMagic || plan[1] != (int32_t)a.plan_key) return;
+    const int n_seg = rec[13];
+    const const_i32* more = plan + (size_t)(1 + kMaxShares + rec[14]) * kRecInts;
+    for (int k = 0; k < n_seg; ++k) {
+        if (k > 0) rec = more + (size_t)(k - 1) * kRecInts;
+        Segment cur;
+        cur.i = rec[0]; cur.kvh = rec[1]; cur.c = rec[2]; cur.q0 = rec[3]; cur.q_len = rec[4]; cur.j0 = rec[5];
+        cur.rows_g = rec[6]; cur.tile_a = rec[7]; cur.tile_e = rec[8];
+        const int flags = rec[9];
+        cur.final_out = (flags & 1) != 0; cur.cut = (flags & 2) != 0;
+        cur.b_first = rec[10]; cur.b_last = rec[11]; cur.slot = rec[12];
+        KVStream st = make_stream<TM, KV8>(a, cur);
+        st.bt_first = rec + 16 - 2 * cur.tile_a;  // entry [page index] of the record's copy
+        attend_dispatch<MTMAX, TM, KV8>(a, cur, st, smem);
+        if (cur.cut) finish_piece<MTMAX>(a, cur, &s_last);
+    }
 }
 
 __device__ __forceinline__ int find_request(const int32_t* __restrict__ cu_q, int B, int row) {
@@ -1143,11 +1276,14 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(GenericArgs a) {
     if (a.lse && lane == 0) a.lse[(size_t)row * a.H_q + h] = m_star + logf(ls);
 }
 
-struct Plan {
-    bool fast;
+// How a call is run.
+struct Setup {
+    bool fast;   // the stream kernel (bf16, D = 128, P = 16, G <= 16, B <= kMaxB); else one wave per (row, head)
     int mt_max;  // 16-row query tiles per row group (template argument of the kernel)
     int nb;      // workgroups of the persistent grid
+    int shares_cap;  // shares the workspace is laid out for
     size_t bytes_o, bytes_ml, bytes_cnt;
+    size_t ws_bytes() const { return bytes_o + bytes_ml + bytes_cnt; }
 };
 
 int validate(const fsr_attn_params* p, const char* who) {
@@ -1166,12 +1302,6 @@ int validate(const fsr_attn_params* p, const char* who) {
     if (p->B > 65535 || p->H_kv > 65535) return fail(FSR_EUNSUP, "%s: B and H_kv are limited to 65535", who);
     if ((long long)p->max_pages * p->P > (1LL << 30)) return fail(FSR_EUNSUP, "%s: max_pages * P exceeds 2^30 tokens", who);
     return FSR_OK;
-}
-
-// A number no earlier call of this process has used (48 bits, never 0).
-unsigned long long next_call_id() {
-    static std::atomic<unsigned long long> counter{0};
-    return (counter.fetch_add(1, std::memory_order_relaxed) + 1) & 0xffffffffffffull;
 }
 
 // Workgroups of the persistent grid: one per compute unit of the current device.
@@ -1194,26 +1324,60 @@ int persistent_blocks() {
     return cached_cus;
 }
 
-Plan make_plan(const fsr_attn_params& p) {
-    Plan pl{};
+// shares_cap: what the partial slots and arrival words are laid out for (the workspace of the ordinary
+// entry points is sized for kMaxShares so that its size does not depend on the device).
+Setup make_setup(const fsr_attn_params& p, int shares_cap = kMaxShares) {
+    Setup su{};
     const int G = p.H_q / p.H_kv;
-    pl.fast = p.dtype == FSR_BF16 && p.D == kD && p.P == kP && G <= 16 && p.B <= kMaxB;
-    if (!pl.fast) return pl;
+    su.fast = p.dtype == FSR_BF16 && p.D == kD && p.P == kP && G <= 16 && p.B <= kMaxB;
+    if (!su.fast) return su;
     // rows of one request that share a KV head: G * max_q_len (unknown bound -> the widest kernel)
     // When they fit four query tiles they are one row group; beyond that (or with no bound given) a
     // request is cut into row groups of up to three tiles, the widest kernel that keeps its
     // accumulators and both K/V tiles in registers without spilling.
     const long long m_rows = p.max_q_len > 0 ? (long long)G * p.max_q_len : 1 << 20;
     const long long mt = (m_rows + 15) / 16;
-    pl.mt_max = mt <= kMaxMT ? (int)mt : 3;
-    // the workspace is sized for up to 1024 workgroups so that its size does not depend on the device
-    pl.nb = std::min(persistent_blocks(), 1024);
-    if (p.max_workgroups > 0) pl.nb = std::min(pl.nb, p.max_workgroups);
-    pl.bytes_o = align_up((size_t)1024 * 2 * 16 * pl.mt_max * kD * sizeof(float), 256);
-    pl.bytes_ml = align_up((size_t)1024 * 2 * 16 * pl.mt_max * 2 * sizeof(float), 256);
-    pl.bytes_cnt = align_up((size_t)(1024 + 1) * sizeof(unsigned long long), 256);
-    return pl;
+    su.mt_max = mt <= kMaxMT ? (int)mt : 3;
+    su.shares_cap = shares_cap;
+    su.nb = std::min(persistent_blocks(), shares_cap);
+    if (p.max_workgroups > 0) su.nb = std::min(su.nb, p.max_workgroups);
+    su.bytes_o = align_up((size_t)shares_cap * 2 * 16 * su.mt_max * kD * sizeof(float), 256);
+    su.bytes_ml = align_up((size_t)shares_cap * 2 * 16 * su.mt_max * 4 * sizeof(float), 256);
+    su.bytes_cnt = align_up((size_t)(shares_cap + 1) * sizeof(unsigned long long), 256);
+    return su;
 }
+
+int cost_base_for(const fsr_attn_params& p, const Setup& su) {
+    return (int)std::min<long long>(kCostBaseMax, std::max<long long>(kCostBase, 2LL * p.B * p.H_kv / su.nb));
+}
+
+// What a plan depends on besides the device arrays it was built from.
+uint32_t plan_key_of(const fsr_attn_params& p, const Setup& su) {
+    uint32_t h = 2166136261u;
+    const int v[] = {p.B, p.N_cap, p.H_q, p.H_kv, p.max_pages, p.n_pages, su.mt_max, su.nb, cost_base_for(p, su), kSegTiles};
+    for (int x : v) {
+        h = (h ^ (uint32_t)x) * 16777619u;
+        h ^= h >> 15;
+    }
+    return h | 1u;
+}
+
+// Segments beyond a share's first that any batch of these shapes can have: every item contributes one
+// segment per share it touches, i.e. at most (items + shares) segments in all.
+size_t plan_more_cap(const fsr_attn_params& p, const Setup& su) {
+    const int G = p.H_q / p.H_kv;
+    const long long per_group = std::max(16 * su.mt_max / G, 1);
+    const long long items = (long long)p.H_kv * ((long long)p.B + p.N_cap / per_group + 1);
+    return (size_t)(items + kMaxShares);
+}
+size_t plan_bytes_of(const fsr_attn_params& p, const Setup& su) {
+    return (size_t)(1 + kMaxShares + plan_more_cap(p, su)) * kRecInts * sizeof(int32_t);
+}
+
+// Plans this process has built: device address -> key.  A host-side record, so that a call handed a
+// buffer that holds no plan, or a plan for other shapes, is refused before anything is launched.
+std::mutex g_plans_mutex;
+std::map<const void*, uint32_t> g_plans;
 
 }  // namespace
 }  // namespace fsr
@@ -1224,68 +1388,109 @@ extern "C" int fsr_attn_workspace_bytes(const fsr_attn_params* p, size_t* out_by
     int rc = validate(p, "fsr_attn_workspace_bytes");
     if (rc != FSR_OK) return rc;
     if (!out_bytes) return fail(FSR_EINVAL, "fsr_attn_workspace_bytes: out_bytes is null");
-    const Plan pl = make_plan(*p);
-    *out_bytes = pl.fast ? pl.bytes_o + pl.bytes_ml + pl.bytes_cnt : 0;
+    const Setup su = make_setup(*p);
+    *out_bytes = su.fast ? su.ws_bytes() : 0;
+    return FSR_OK;
+}
+
+extern "C" int fsr_attn_path(const fsr_attn_params* p) {
+    int rc = validate(p, "fsr_attn_path");
+    if (rc != FSR_OK) return rc;
+    return make_setup(*p).fast ? FSR_PATH_STREAM : FSR_PATH_GENERIC;
+}
+
+extern "C" int fsr_attn_plan_bytes(const fsr_attn_params* p, size_t* out_bytes) {
+    int rc = validate(p, "fsr_attn_plan_bytes");
+    if (rc != FSR_OK) return rc;
+    if (!out_bytes) return fail(FSR_EINVAL, "fsr_attn_plan_bytes: out_bytes is null");
+    const Setup su = make_setup(*p);
+    *out_bytes = su.fast ? plan_bytes_of(*p, su) : 0;
     return FSR_OK;
 }
 
 namespace {
-// Both entry points: kv8 = the caches hold E4M3 bytes with per-head scales (fast path only).
+void fill_common(FastArgs& a, const fsr_attn_params* p, const Setup& su, const int32_t* block_tables, const int32_t* ctx_lens,
+                 const int32_t* cu_q) {
+    a.bt = block_tables; a.ctx = ctx_lens; a.cu_q = cu_q;
+    a.B = p->B; a.H_q = p->H_q; a.H_kv = p->H_kv; a.G = p->H_q / p->H_kv;
+    a.max_pages = p->max_pages; a.n_pages = p->n_pages;
+    a.nb = su.nb; a.m_cap = 16 * su.mt_max;
+    a.seg_tiles = kSegTiles;
+    a.cost_base = cost_base_for(*p, su);
+    a.plan = nullptr; a.plan_key = 0;
+}
+
+// All attention entry points.  kv8: the caches hold E4M3 bytes with per-head scales (stream kernel only).
+// plan: schedule built by fsr_attn_plan for the same shapes and device arrays, or null.
 int attention_call(const void* q, const void* k_cache, const void* v_cache, const float* k_scale, const float* v_scale, bool kv8,
                    const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q, void* out, float* lse,
-                   const fsr_attn_params* p, void* workspace, size_t ws_bytes, void* stream) {
-    int rc = validate(p, "fsr_verify_attention");
+                   const fsr_attn_params* p, const void* plan, void* workspace, size_t ws_bytes, int shares_cap, void* stream,
+                   const char* who) {
+    int rc = validate(p, who);
     if (rc != FSR_OK) return rc;
     if (p->B == 0 || p->N_cap == 0) return FSR_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !ctx_lens || !cu_q || !out)
-        return fail(FSR_EINVAL, "fsr_verify_attention: null pointer among q/k_cache/v_cache/block_tables/ctx_lens/cu_q/out");
-    if (kv8 && (!k_scale || !v_scale)) return fail(FSR_EINVAL, "fsr_verify_attention_kv8: k_scale / v_scale is null");
+        return fail(FSR_EINVAL, "%s: null pointer among q/k_cache/v_cache/block_tables/ctx_lens/cu_q/out", who);
+    if (kv8 && (!k_scale || !v_scale)) return fail(FSR_EINVAL, "%s: k_scale / v_scale is null", who);
     hipStream_t s = (hipStream_t)stream;
-    const Plan pl = make_plan(*p);
-    if (kv8 && !pl.fast)
-        return fail(FSR_EUNSUP, "fsr_verify_attention_kv8: 8-bit caches need bf16 queries, D = 128, P = 16, H_q / H_kv <= 16, B <= %d", kMaxB);
-    if (pl.fast) {
-        const size_t need = pl.bytes_o + pl.bytes_ml + pl.bytes_cnt;
-        if (!workspace || ws_bytes < need) return fail(FSR_EWS, "fsr_verify_attention: workspace %zu bytes, need %zu", ws_bytes, need);
-        if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "fsr_verify_attention: workspace must be 256-byte aligned");
+    const Setup su = make_setup(*p, shares_cap);
+    if (kv8 && !su.fast)
+        return fail(FSR_EUNSUP, "%s: 8-bit caches need bf16 queries, D = 128, P = 16, H_q / H_kv <= 16, B <= %d", who, kMaxB);
+    if (plan && !su.fast)
+        return fail(FSR_EUNSUP, "%s: a plan needs the stream kernel (bf16, D = 128, P = 16, H_q / H_kv <= 16, B <= %d)", who, kMaxB);
+    if (su.fast) {
+        const size_t need = su.ws_bytes();
+        if (!workspace || ws_bytes < need) return fail(FSR_EWS, "%s: workspace %zu bytes, need %zu", who, ws_bytes, need);
+        if ((uintptr_t)workspace & 255) return fail(FSR_EWS, "%s: workspace must be 256-byte aligned", who);
         if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15)
-            return fail(FSR_EINVAL, "fsr_verify_attention: q/k_cache/v_cache/out must be 16-byte aligned");
+            return fail(FSR_EINVAL, "%s: q/k_cache/v_cache/out must be 16-byte aligned", who);
         FastArgs a;
+        fill_common(a, p, su, block_tables, ctx_lens, cu_q);
         a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache; a.v = (const uint16_t*)v_cache;
-        a.bt = block_tables; a.ctx = ctx_lens; a.cu_q = cu_q;
         a.out = out; a.lse = lse;
         a.part_o = (float*)workspace;
-        a.part_ml = (float*)((char*)workspace + pl.bytes_o);
-        a.arrivals = (unsigned long long*)((char*)workspace + pl.bytes_o + pl.bytes_ml);
+        a.part_ml = (float*)((char*)workspace + su.bytes_o);
+        a.arrivals = (unsigned long long*)((char*)workspace + su.bytes_o + su.bytes_ml);
         a.call_id = next_call_id();
-        a.B = p->B; a.H_q = p->H_q; a.H_kv = p->H_kv; a.G = p->H_q / p->H_kv;
-        a.max_pages = p->max_pages; a.n_pages = p->n_pages;
-        a.nb = pl.nb; a.m_cap = 16 * pl.mt_max; a.out_bf16 = p->out_dtype == FSR_BF16;
+        a.out_bf16 = p->out_dtype == FSR_BF16;
         a.scale_log2 = p->scale * kLog2e;
         a.k_scale = k_scale; a.v_scale = v_scale;
-        a.seg_tiles = kSegTiles;
-        a.cost_base = (int)std::min<long long>(kCostBaseMax, std::max<long long>(kCostBase, 2LL * p->B * p->H_kv / pl.nb));
-#ifdef FSR_TIMING
-        a.dbg = (long long*)((char*)workspace + need);  // the timing build expects 1 MiB of slack after the workspace
-#endif
-        const dim3 grid(pl.nb), block(kThreads);
-#define FSR_LAUNCH(MT)                                                                              \
-    if (kv8 && p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                  \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, true, true>), grid, block, kFastSmem, s, a);     \
-    else if (kv8)                                                                                   \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, false, true>), grid, block, kFastSmem, s, a);    \
-    else if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                                    \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, true, false>), grid, block, kFastSmem, s, a);    \
-    else                                                                                            \
-        hipLaunchKernelGGL((attn_stream_kernel<MT, false, false>), grid, block, kFastSmem, s, a)
-        switch (pl.mt_max) {
+        if (plan) {
+            const uint32_t key = plan_key_of(*p, su);
+            {
+                std::lock_guard<std::mutex> lock(g_plans_mutex);
+                const auto it = g_plans.find(plan);
+                if (it == g_plans.end()) return fail(FSR_EINVAL, "%s: no plan has been built in this buffer (fsr_attn_plan)", who);
+                if (it->second != key)
+                    return fail(FSR_ESHAPE, "%s: the plan was built for other shapes (B, N_cap, heads, max_pages, n_pages, max_q_len, max_workgroups)", who);
+            }
+            if ((uintptr_t)plan & 15) return fail(FSR_EINVAL, "%s: plan must be 16-byte aligned", who);
+            a.plan = (const int32_t*)plan;
+            a.plan_key = key;
+        }
+        const dim3 grid(su.nb), block(kThreads);
+        const size_t smem = plan ? kFixedSmem : sched_smem(p->B);
+#define FSR_LAUNCH_K(KERNEL, MT)                                                             \
+    if (kv8 && p->kv_layout == FSR_KV_TOKEN_MAJOR)                                           \
+        hipLaunchKernelGGL((KERNEL<MT, true, true>), grid, block, smem, s, a);               \
+    else if (kv8)                                                                            \
+        hipLaunchKernelGGL((KERNEL<MT, false, true>), grid, block, smem, s, a);              \
+    else if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                             \
+        hipLaunchKernelGGL((KERNEL<MT, true, false>), grid, block, smem, s, a);              \
+    else                                                                                     \
+        hipLaunchKernelGGL((KERNEL<MT, false, false>), grid, block, smem, s, a)
+#define FSR_LAUNCH(MT)                                    \
+    if (plan) { FSR_LAUNCH_K(attn_planned_kernel, MT); }  \
+    else { FSR_LAUNCH_K(attn_stream_kernel, MT); }
+        switch (su.mt_max) {
             case 1: FSR_LAUNCH(1); break;
             case 2: FSR_LAUNCH(2); break;
             case 3: FSR_LAUNCH(3); break;
             default: FSR_LAUNCH(4); break;
         }
 #undef FSR_LAUNCH
-        return check_launch("attn_stream_kernel");
+#undef FSR_LAUNCH_K
+        return check_launch(plan ? "attn_planned_kernel" : "attn_stream_kernel");
     }
     GenericArgs g;
     g.q = q; g.k = k_cache; g.v = v_cache; g.bt = block_tables; g.ctx = ctx_lens; g.cu_q = cu_q; g.out = out; g.lse = lse;
@@ -1293,7 +1498,7 @@ int attention_call(const void* q, const void* k_cache, const void* v_cache, cons
     g.scale = p->scale;
     g.token_major = p->kv_layout == FSR_KV_TOKEN_MAJOR;
     const dim3 grid(p->H_q, p->N_cap), block(64);
-    if (p->N_cap > 65535) return fail(FSR_EUNSUP, "fsr_verify_attention: generic path is limited to N_cap <= 65535 rows");
+    if (p->N_cap > 65535) return fail(FSR_EUNSUP, "%s: the one-wave-per-row path is limited to N_cap <= 65535 rows", who);
     const bool bf_in = p->dtype == FSR_BF16, bf_out = p->out_dtype == FSR_BF16;
     if (p->D == 64) {
         if (!bf_in) hipLaunchKernelGGL((attn_generic_kernel<float, float, 64>), grid, block, 0, s, g);
@@ -1313,14 +1518,48 @@ extern "C" int fsr_verify_attention(const void* q, const void* k_cache, const vo
                                     const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
                                     void* workspace, size_t ws_bytes, void* stream) {
     (void)spec_lens;
-    return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, workspace,
-                          ws_bytes, stream);
+    return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, nullptr, workspace,
+                          ws_bytes, kMaxShares, stream, "fsr_verify_attention");
 }
 
 extern "C" int fsr_verify_attention_kv8(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
                                         const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
                                         const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
                                         void* workspace, size_t ws_bytes, void* stream) {
-    return attention_call(q, k_cache, v_cache, k_scale, v_scale, true, block_tables, ctx_lens, cu_q, out, lse, p, workspace,
-                          ws_bytes, stream);
+    return attention_call(q, k_cache, v_cache, k_scale, v_scale, true, block_tables, ctx_lens, cu_q, out, lse, p, nullptr, workspace,
+                          ws_bytes, kMaxShares, stream, "fsr_verify_attention_kv8");
+}
+
+extern "C" int fsr_attn_plan(const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q,
+                             const fsr_attn_params* p, void* plan, size_t plan_bytes, void* stream) {
+    int rc = validate(p, "fsr_attn_plan");
+    if (rc != FSR_OK) return rc;
+    if (!block_tables || !ctx_lens || !cu_q || !plan) return fail(FSR_EINVAL, "fsr_attn_plan: null pointer among block_tables/ctx_lens/cu_q/plan");
+    const Setup su = make_setup(*p);
+    if (!su.fast)
+        return fail(FSR_EUNSUP, "fsr_attn_plan: only the stream kernel takes a plan (bf16, D = 128, P = 16, H_q / H_kv <= 16, B <= %d)", kMaxB);
+    const size_t need = plan_bytes_of(*p, su);
+    if (plan_bytes < need) return fail(FSR_EWS, "fsr_attn_plan: plan buffer %zu bytes, need %zu", plan_bytes, need);
+    if ((uintptr_t)plan & 15) return fail(FSR_EINVAL, "fsr_attn_plan: plan must be 16-byte aligned");
+    FastArgs a{};
+    fill_common(a, p, su, block_tables, ctx_lens, cu_q);
+    a.plan_key = plan_key_of(*p, su);
+    const size_t smem = sched_smem(p->B) + (size_t)kMaxShares * sizeof(int);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kThreads), smem, (hipStream_t)stream, a, su.mt_max, (int32_t*)plan,
+                       (int)plan_more_cap(*p, su));
+    rc = check_launch("attn_plan_kernel");
+    if (rc == FSR_OK) {
+        std::lock_guard<std::mutex> lock(g_plans_mutex);
+        g_plans[plan] = a.plan_key;
+    }
+    return rc;
+}
+
+extern "C" int fsr_verify_attention_planned(const void* q, const void* k_cache, const void* v_cache,
+                                            const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q,
+                                            void* out, float* lse, const fsr_attn_params* p, const void* plan,
+                                            void* workspace, size_t ws_bytes, void* stream) {
+    if (!plan) return fail(FSR_EINVAL, "fsr_verify_attention_planned: plan is null");
+    return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, plan, workspace,
+                          ws_bytes, kMaxShares, stream, "fsr_verify_attention_planned");
 }

@@ -70,6 +70,25 @@ def test_host_detectable_errors(lib):
     one = ctypes.c_void_p(256)  # never dereferenced: the workspace check comes first
     assert lib.fsr_verify_attention(one, one, one, one, one, None, one, one, None, ctypes.byref(ok), None,
                                     ctypes.c_size_t(0), None) == -4
+    # which kernel a shape takes, and the plan calls' host checks
+    assert lib.fsr_attn_path(ctypes.byref(ok)) == 1
+    gen = b.AttnParams.from_buffer_copy(ok); gen.D = 64
+    assert lib.fsr_attn_path(ctypes.byref(gen)) == 0
+    gen = b.AttnParams.from_buffer_copy(ok); gen.dtype = 0; gen.out_dtype = 0
+    assert lib.fsr_attn_path(ctypes.byref(gen)) == 0
+    assert lib.fsr_attn_path(None) == -1
+    assert lib.fsr_attn_plan_bytes(ctypes.byref(ok), ctypes.byref(out)) == 0 and out.value >= 33 * 128
+    assert lib.fsr_attn_plan_bytes(ctypes.byref(gen), ctypes.byref(out)) == 0 and out.value == 0
+    assert lib.fsr_attn_plan(one, one, one, ctypes.byref(gen), one, ctypes.c_size_t(1 << 20), None) == -3   # not the stream kernel
+    assert lib.fsr_attn_plan(one, one, one, ctypes.byref(ok), one, ctypes.c_size_t(64), None) == -4         # buffer too small
+    assert lib.fsr_attn_plan(one, one, None, ctypes.byref(ok), one, ctypes.c_size_t(1 << 20), None) == -1   # cu_q null
+    ws = ctypes.c_size_t(0)
+    assert lib.fsr_attn_workspace_bytes(ctypes.byref(ok), ctypes.byref(ws)) == 0
+    assert lib.fsr_verify_attention_planned(one, one, one, one, one, one, one, None, ctypes.byref(ok), None, one, ws, None) == -1
+    # a buffer in which no plan was built is refused before the launch
+    assert lib.fsr_verify_attention_planned(one, one, one, one, one, one, one, None, ctypes.byref(ok), ctypes.c_void_p(4096),
+                                            one, ws, None) == -1
+    assert b"no plan" in lib.fsr_last_error()
     acc = b.AcceptParams(B=4, V=0, S_max=2, mode=0, temperature=1.0, dtype=0, reserved2=0)
     assert lib.fsr_accept_workspace_bytes(ctypes.byref(acc), ctypes.byref(out)) == -1
     acc.V = 1000; acc.mode = 7

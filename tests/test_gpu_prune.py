@@ -78,3 +78,38 @@ def test_prune_wide_rows_16B_path(fsr, oracle):
     keep = (rng.random(N) < 0.6).astype(np.uint8)
     pay = rng.integers(-2**31, 2**31 - 1, size=(N, 2048), dtype=np.int64).astype(np.int32)  # 8 KB rows
     _compare(fsr, oracle, keep, cu, True, pay, N)
+
+
+@pytest.mark.parametrize("seed,B,maxlen", [(0, 1, 5), (1, 37, 9), (2, 700, 11), (3, 2500, 4)])
+def test_survivor_compact_equals_mask_then_compact(fsr, oracle, seed, B, maxlen):
+    """The one-call form (accepted lengths in, re-packed batch out) against the oracle's mask + compaction and
+    against the two separate calls, bit for bit; invalid requests (accepted_len = -1) keep nothing."""
+    announce(f"survivor_compact seed={seed} B={B}")
+    rng = np.random.default_rng(100 + seed)
+    lens = rng.integers(0, maxlen + 1, size=B)
+    cu = workloads.exclusive_offsets(lens)
+    N = int(cu[-1])
+    N_cap = N + 3
+    acc = rng.integers(-1, maxlen + 2, size=B).astype(np.int32)      # some beyond the request's rows, some -1
+    pay = rng.integers(-1000, 1000, size=(N_cap, 8)).astype(np.int32)
+    keep_ref = np.concatenate([np.arange(l) <= a for l, a in zip(lens, acc)] + [np.zeros(0, bool)]).astype(np.uint8)
+    ref = oracle.prune_compact(keep_ref, cu, suffix_close=True, payload=pay[:N])
+    keep_d = torch.full((N_cap,), 9, dtype=torch.uint8, device="cuda")
+    r = fsr.survivor_compact(dev(acc), dev(cu), N_cap, keep_mask=keep_d, payload=dev(pay))
+    keep2 = torch.full((N_cap,), 9, dtype=torch.uint8, device="cuda")
+    fsr.survivor_mask(dev(acc), dev(cu), keep2)
+    r2 = fsr.prune_compact(keep2, dev(cu), suffix_close=True, payload=dev(pay))
+    torch.cuda.synchronize()
+    n_new = int(ref["new_cu_q"][-1])
+    assert np.array_equal(keep_d.cpu().numpy()[:N], keep_ref) and (keep_d.cpu().numpy()[N:] == 9).all()
+    assert torch.equal(keep_d, keep2)
+    for name in ("new_cu_q", "new_q_lens", "src_row", "dst_row", "n_active", "active_ids"):
+        assert torch.equal(r[name], r2[name]), name
+    assert np.array_equal(r["new_cu_q"].cpu().numpy(), ref["new_cu_q"])
+    assert np.array_equal(r["src_row"].cpu().numpy()[:N], ref["src_row"])
+    assert np.array_equal(r["dst_row"].cpu().numpy()[:N], ref["dst_row"])
+    assert np.array_equal(r["payload"].cpu().numpy()[:n_new], ref["payload"])
+    # without the optional mask output
+    r3 = fsr.survivor_compact(dev(acc), dev(cu), N_cap)
+    torch.cuda.synchronize()
+    assert torch.equal(r3["src_row"], r["src_row"])
