@@ -153,6 +153,23 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
                          void* stream);
 
 /*
+ * fsr_verify_attention for callers that cannot allocate device memory or be handed a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * minus spec_lens and the workspace; same kernels, same results.  The partial results and arrival
+ * counters that the workspace would hold live in a buffer built into the library
+ * (fsr_static_scratch_bytes() bytes, about 17 MB, resident on every GPU the library runs on until the
+ * process ends), laid out for a grid of at most 256 workgroups.  The call allocates and frees nothing.
+ * Shapes whose scratch would not fit return FSR_EWS before anything is launched.  All calls on one
+ * GPU share that buffer: calls that can overlap in time on one GPU (different streams) race; on one
+ * stream they may follow each other freely (nothing needs clearing between calls).
+ */
+size_t fsr_static_scratch_bytes(void);
+int fsr_verify_attention_static(const void* q, const void* k_cache, const void* v_cache,
+                                const int32_t* block_tables, const int32_t* ctx_lens,
+                                const int32_t* cu_q, void* out, float* lse,
+                                const fsr_attn_params* p /*host*/, void* stream);
+
+/*
  * Which kernel fsr_verify_attention runs for shapes *p (host query, no GPU work): FSR_PATH_STREAM,
  * the HBM-bandwidth kernel (bf16, D = 128, P = 16, H_q / H_kv <= 16, B <= 4096), or
  * FSR_PATH_GENERIC, one wavefront per (row, head) for every other supported shape (fp32 inputs,

@@ -22,7 +22,7 @@ KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
 
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_attn_path", "fsr_attn_plan_bytes", "fsr_attn_plan",
-    "fsr_verify_attention_planned", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
+    "fsr_verify_attention_planned", "fsr_verify_attention_static", "fsr_static_scratch_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_survivor_compact", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
 ]
@@ -72,6 +72,7 @@ def load_library():
         lib.fsr_version.restype = ctypes.c_char_p
         for name in SYMBOLS[2:]:
             getattr(lib, name).restype = ctypes.c_int
+        lib.fsr_static_scratch_bytes.restype = ctypes.c_size_t
         _lib = lib
     return _lib
 
@@ -202,6 +203,23 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
         _ptr(spec_lens, torch.int32, "spec_lens"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"),
         _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _ptr(workspace, name="workspace"),
         ctypes.c_size_t(ws_bytes), _stream()))
+    return out, lse
+
+
+def verify_attention_static(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *, scale, out, lse=None, max_q_len=0,
+                            max_workgroups=0, kv_layout=KV_HEAD_MAJOR):
+    """fsr_verify_attention_static: no workspace argument and no allocation, here or in the library (`out` is
+    the caller's).  Returns (out, lse)."""
+    B = ctx_lens.shape[0]
+    p = _attn_params(q, k_cache, block_tables, B, out.dtype, scale, max_q_len, max_workgroups, kv_layout)
+    if v_cache.shape != k_cache.shape or v_cache.dtype != k_cache.dtype or k_cache.dtype != q.dtype:
+        raise ValueError("q, k_cache and v_cache must share dtype; caches must share shape")
+    if cu_q.shape[0] != B + 1 or block_tables.shape[0] != B or out.shape != q.shape:
+        raise ValueError("cu_q must have B+1 entries, block_tables B rows, out the shape of q")
+    _check(load_library().fsr_verify_attention_static(
+        _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+        _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+        _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"), _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _stream()))
     return out, lse
 
 

@@ -1563,3 +1563,66 @@ extern "C" int fsr_verify_attention_planned(const void* q, const void* k_cache, 
     return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, plan, workspace,
                           ws_bytes, kMaxShares, stream, "fsr_verify_attention_planned");
 }
+
+// ---------------------------------------------------------------------------------------
+// fsr_verify_attention_static: the same call for callers that cannot allocate (or be handed) a
+// workspace.  The partial slots and arrival words live in a file-scope device array, laid out for
+// kStaticShares workgroups (MI355X has 256 compute units; a device with more runs a 256-workgroup
+// grid here).  Every GPU holds its own copy of the array at its own address, looked up once per
+// device; all calls on a GPU share it, so calls that overlap in time on one GPU race.
+// ---------------------------------------------------------------------------------------
+namespace {
+constexpr int kStaticShares = 256;
+constexpr size_t kStaticScratchBytes =
+    (size_t)kStaticShares * 2 * 16 * kMaxMT * (kD + 4) * sizeof(float) + (size_t)(kStaticShares + 1) * sizeof(unsigned long long) + 3 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (0 on failure, with the error text set).
+void* static_scratch() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        fail(FSR_EHIP, "fsr_verify_attention_static: hipGetDevice: %s", hipGetErrorString(e));
+        return nullptr;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        fail(FSR_EUNSUP, "fsr_verify_attention_static: device index %d (at most %d devices)", dev, kMaxDevices);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(FSR_EHIP, "fsr_verify_attention_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" size_t fsr_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int fsr_verify_attention_static(const void* q, const void* k_cache, const void* v_cache,
+                                           const int32_t* block_tables, const int32_t* ctx_lens, const int32_t* cu_q,
+                                           void* out, float* lse, const fsr_attn_params* p, void* stream) {
+    int rc = validate(p, "fsr_verify_attention_static");
+    if (rc != FSR_OK) return rc;
+    const Setup su = make_setup(*p, kStaticShares);
+    if (!su.fast)  // the one-wave-per-row kernel uses no scratch buffer at all
+        return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, nullptr, nullptr, 0,
+                              kStaticShares, stream, "fsr_verify_attention_static");
+    if (su.ws_bytes() > kStaticScratchBytes)
+        return fail(FSR_EWS, "fsr_verify_attention_static: these shapes need %zu bytes of scratch, the built-in buffer has %zu",
+                    su.ws_bytes(), kStaticScratchBytes);
+    void* ws = static_scratch();
+    if (!ws) return FSR_EHIP;
+    return attention_call(q, k_cache, v_cache, nullptr, nullptr, false, block_tables, ctx_lens, cu_q, out, lse, p, nullptr, ws,
+                          kStaticScratchBytes, kStaticShares, stream, "fsr_verify_attention_static");
+}
