@@ -11,10 +11,13 @@ from the last-level cache.  The step is captured once into a HIP graph and repla
 
 ``--workload 3|4|5`` runs the same one-shot step at the batch shapes of the other configurations
 (their layers cycle through as many distinct caches as fit 16 GB); the metric is quoted on the default.
+``--workload 4|5 --chunked`` runs those configurations' own schedules instead: two chunks (workload 4)
+or frontiers of two drafts (workload 5), each chunk = row selection, attention over every layer on the
+chunk's rows only, accept, commit; K/V of a request are read again by every chunk it takes part in.
 
 Prints ONE JSON line: verified draft tokens/s (sum of the speculative lengths submitted per
-step / step time), the HBM roofline of the dominant kernel (attention), and the CPU oracle
-timed beside it on the host cores.
+step / step time), the HBM roofline of the dominant kernel (attention), per-kernel figures for the
+other calls of the step ("kernels"), and the CPU oracle timed beside it on the host cores.
 """
 from __future__ import annotations
 
@@ -109,9 +112,116 @@ def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=
         attention_all_layers()
         tail()
 
+    def accept_only():
+        fsr.spec_accept(p_t, p_d, toks, u_a, u_s, cu_q, cu_d, S_max=S_max, accepted_len=acc, n_emitted=nem, emitted=em,
+                        workspace=ws_acc)
+
+    def compact_only():
+        fsr.survivor_compact(acc, cu_q, b.N, keep_mask=keep, payload=out, payload_out=packed, out=prune_out)
+
+    rank = torch.empty(max(int(b.cu_d[-1]), 1), **i32)
+
+    def rank_only():  # early-exit check on the step's target rows (stand-ins for intermediate scores); not part of the step
+        fsr.topk_rank_check(p_t, toks, cu_q, cu_d, K=10, rank=rank[:int(b.cu_d[-1])], keep_mask=keep)
+
     state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed,
-                 n_caches=n_caches, kv_bytes=kv_bytes)
+                 n_caches=n_caches, kv_bytes=kv_bytes, k_caches=k_caches, v_caches=v_caches,
+                 dev=dict(bt=bt, ctx=ctx, spec=spec, cu_q=cu_q, cu_d=cu_d, p_t=p_t, p_d=p_d, toks=toks, u_a=u_a, u_s=u_s),
+                 calls=dict(accept=accept_only, compact=compact_only, rank=rank_only))
     return step, attention_all_layers, tail, state
+
+
+def kernel_figures(b, st, times_us):
+    """Algorithmic bytes of the step's other calls (what the method must move, from this batch's own outcome) next
+    to their measured durations.  accept (PROBS): 8 bytes of gathers per draft + one target row (bonus) or one
+    target and one draft row (rejection) per request; compaction: mask + offsets in, maps out, the surviving
+    payload rows in and out; rank check: one score row per draft."""
+    acc = st["acc"].cpu().numpy()
+    d = b.spec_lens.astype(np.int64)
+    rows = np.where(acc < d, 2, 1)                 # every request here has its bonus row
+    accept_bytes = int((rows * 4 * b.V + 8 * d).sum())
+    n_new = int(st["prune"]["new_cu_q"][-1].item())
+    row_bytes = b.H_q * b.D * 2
+    compact_bytes = b.N + 4 * (b.B + 1) + 4 * (2 * b.N + 3 * b.B) + b.N + 2 * n_new * row_bytes
+    rank_bytes = int(d.sum()) * 4 * b.V
+
+    def fig(us, nbytes, launches, note):
+        gbs = nbytes / us / 1e3
+        return dict(us=us, launches=launches, algorithmic_bytes=nbytes, achieved_GBs=gbs, frac_of_hbm_peak=gbs / HBM_PEAK_GBS,
+                    note=note)
+
+    return {
+        "spec_accept": fig(times_us["accept"], accept_bytes, 2, "accept_decide_kernel + accept_sample_kernel"),
+        "survivor_compact": fig(times_us["compact"], compact_bytes, 2,
+                                f"prune_scan_kernel + gather_rows_kernel; {n_new} of {b.N} rows of {row_bytes} bytes survive"),
+        "topk_rank_check": fig(times_us["rank"], rank_bytes, 3,
+                               "rank_init + rank_count + rank_mask over the target rows, K = 10; not part of the timed step"),
+    }
+
+
+def chunked_run(args, fsr, torch, workloads, b):
+    """The configuration's own chunked schedule (Sec. 3.3), every buffer preallocated, whole step in one HIP graph.
+    Returns (ms per step, per-chunk table, attention totals)."""
+    from paper_2604_20503_amd.frontier import ChunkedVerifier
+
+    step, _, _, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=False)
+    del step
+    d = st["dev"]
+    chunks = workloads.chunk_plan(args.workload, b.spec_lens)
+    dev_chunks = [torch.from_numpy(c).cuda() for c in chunks]
+    layers = [(st["k_caches"][l % st["n_caches"]], st["v_caches"][l % st["n_caches"]]) for l in range(args.layers)]
+    v = ChunkedVerifier(q=st["q"], k_caches=[k for k, _ in layers], v_caches=[x for _, x in layers], block_tables=d["bt"],
+                        ctx_lens=d["ctx"], spec_lens=d["spec"], cu_q=d["cu_q"], cu_d=d["cu_d"], p_target=d["p_t"],
+                        p_draft=d["p_d"], draft_tokens=d["toks"], u_accept=d["u_a"], u_sample=d["u_s"], chunks=dev_chunks,
+                        scale=b.scale, out=st["out"], S_total_max=b.S_max, chunk_S_max=int(max(c.max() for c in chunks)),
+                        use_plan=not args.no_plan)
+    stream = torch.cuda.Stream()
+    table = [dict() for _ in chunks]
+    ev = {}
+    with torch.cuda.stream(stream):
+        # eager pass 1: what every chunk works on (read back between chunks; never part of a timed run)
+        def look(stage, k, s):
+            if stage != "attn_end":
+                return
+            stream.synchronize()
+            ql = s.tsel["new_q_lens"].cpu().numpy().astype(np.int64)
+            cc = s.chunk_ctx.cpu().numpy().astype(np.int64)
+            act = ql > 0
+            tok = (cc + ql)[act]
+            table[k].update(rows=int(ql.sum()), requests=int(act.sum()), kv_tokens=int(tok.sum()),
+                            attention_bytes_per_layer=int(2 * tok.sum() * b.H_kv * b.D * 2 + 2 * ql.sum() * b.H_q * b.D * 2 +
+                                                          4 * ((tok + b.P - 1) // b.P).sum()))
+        res = v.run(mark=look)
+        stream.synchronize()
+        # eager pass 2: HIP events around every chunk's attention layers
+        for _ in range(2):
+            def stamp(stage, k, s):
+                if stage in ("attn_begin", "attn_end"):
+                    e = torch.cuda.Event(enable_timing=True)
+                    e.record(stream)
+                    ev[(stage, k)] = e
+            v.run(mark=stamp)
+            stream.synchronize()
+        for k in range(len(chunks)):
+            us = ev[("attn_begin", k)].elapsed_time(ev[("attn_end", k)]) * 1e3 / args.layers
+            table[k]["attention_us_per_layer"] = us
+            table[k]["achieved_GBs"] = table[k]["attention_bytes_per_layer"] / us / 1e3 if us > 0 else 0.0
+        # the timed region: the whole step as one graph
+        run = v.run
+        if not args.no_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                v.run()
+            run = g.replay
+        for _ in range(max(1, args.warmup)):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / args.steps, table, res, st, chunks
 
 
 def cpu_baseline(b, n_layers):
@@ -226,17 +336,19 @@ def overlap_measure(fsr, torch, workloads, b, n_layers, n_draft_cus, reps=5):
     return res
 
 
-def measured_traffic(workload):
-    """HBM bytes per attention launch from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE, scaled by a plain copy of known size), or None if there is no summary."""
-    path = os.path.join(ROOT, "profiles", f"attn_stream_kernel_cfg{workload}_hbm_traffic.txt")
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+    scaled by a plain copy of known size) and the file it came from, or (None, None) if there is no summary for
+    this kernel and workload.  A figure measured on an earlier build of the kernel is still that build's: the
+    summary names the commit."""
+    rel = os.path.join("profiles", f"{kernel}_cfg{workload}_hbm_traffic.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                return float(line.split(":", 1)[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def main():
@@ -244,10 +356,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--layers", type=int, default=N_LAYERS)
+    ap.add_argument("--layers", type=int, default=0,
+                    help="attention calls per step; default: 32 (Llama-3-8B depth), 80 for workload 4 (70B depth)")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5],
                     help="workload configuration; 2 (the default) is the one the metric is quoted on, the others "
                          "run the same one-shot step at their batch shapes")
+    ap.add_argument("--chunked", action="store_true",
+                    help="workloads 4 and 5: run the configuration's own chunked schedule (two chunks / frontiers of two "
+                         "drafts with accept and row pruning after each) instead of the one-shot step")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true",
@@ -263,6 +379,11 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.chunked and args.workload not in (4, 5):
+        print("bench.py: --chunked is the schedule of workloads 4 and 5", file=sys.stderr)
+        sys.exit(2)
+    if args.layers <= 0:
+        args.layers = 80 if args.workload == 4 else N_LAYERS
 
     import torch
     import paper_2604_20503_amd as fsr
@@ -271,7 +392,8 @@ def main():
     fsr.load_library()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
     b = workloads.make_batch(args.workload)
-    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=not args.no_plan)
+    drafts = int(b.spec_lens.sum())
+    attn_kernel = "attn_stream_kernel" if args.no_plan else "attn_planned_kernel"
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
@@ -281,6 +403,40 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.chunked:
+        ms_per_step, table, res, st, chunks = chunked_run(args, fsr, torch, workloads, b)
+        attn_bytes = sum(t["attention_bytes_per_layer"] for t in table)
+        attn_us = sum(t["attention_us_per_layer"] for t in table)
+        achieved = attn_bytes / attn_us / 1e3
+        one_shot_bytes = b.attention_bytes()
+        result = {
+            "metric": "verified_draft_tokens_per_s", "value": drafts / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": WORKLOADS[args.workload].replace(", one-shot", "").replace(" shapes, one-shot", ""),
+                       "schedule": f"chunked: {len(chunks)} chunks, accept + row pruning after each",
+                       "layers_per_step": args.layers, "rows": b.N, "drafts_per_step": drafts,
+                       "launch": "eager" if args.no_graph else "hip_graph", "seed": b.seed,
+                       "distinct_kv_caches": st["n_caches"], "kv_cache_bytes": st["kv_bytes"],
+                       "rows_computed": sum(t["rows"] for t in table),
+                       "kv_bytes_read_vs_one_shot": attn_bytes / one_shot_bytes, "chunks": table},
+            "roofline": {"bound": "hbm", "kernel": f"{attn_kernel} (verify_attention, one launch per layer and chunk; all chunks)",
+                         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "traffic": None, "algorithmic_bytes_per_launch": attn_bytes / len(table),
+                         "launch_us": attn_us / len(table)},
+        }
+        if not args.no_cpu_baseline:
+            base, ref = cpu_baseline(b, args.layers)
+            result["cpu_baseline"] = base
+            result["cpu_baseline"]["sample"] += "; the oracle's one-shot step (the chunked schedule emits the same tokens)"
+            result["config"]["accept_matches_oracle"] = bool(
+                np.array_equal(res["accepted_len"].cpu().numpy(), ref["accepted_len"]) and
+                np.array_equal(res["n_emitted"].cpu().numpy(), ref["n_emitted"]))
+            result["config"]["accepted_drafts_per_step"] = int(ref["accepted_len"].sum())
+        print(json.dumps(result))
+        return
+
+    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=not args.no_plan)
     stream = torch.cuda.Stream()
     graph = None
     with torch.cuda.stream(stream):
@@ -303,8 +459,9 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
 
-        # dominant kernel: attention.  HIP events on the launch stream around the layer loop of
-        # every timed repetition; average duration of one attention call (all its kernels).
+        # Per-call figures: HIP events on the launch stream around a graph (or eager run) of that call alone,
+        # once per timed repetition.  Dominant: attention, the layer loop divided by the layer count (with a
+        # plan, the step's one plan launch is inside that figure).
         def timed(fn):
             runner = fn
             if graph is not None:
@@ -323,26 +480,31 @@ def main():
 
         attn_ms = timed(attn_only) / args.layers
         tail_ms = timed(tail)
+        call_us = {name: timed(fn) * 1e3 for name, fn in st["calls"].items()}
+        run()  # leave the step's own outcome in the buffers (the rank check above reuses the mask buffer)
+        torch.cuda.synchronize()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    drafts = int(b.spec_lens.sum())
     value = drafts / (ms_per_step * 1e-3)
     attn_bytes = b.attention_bytes()
     achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+    traffic, traffic_src = measured_traffic(attn_kernel, args.workload)
 
     result = {
         "metric": "verified_draft_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.workload],
+        "config": {"workload": WORKLOADS[args.workload], "schedule": "one-shot",
                    "layers_per_step": args.layers, "rows": b.N, "drafts_per_step": drafts,
                    "kv_tokens": b.kv_tokens(), "launch": "hip_graph" if graph is not None else "eager",
                    "attention_ms_per_layer": attn_ms, "accept_prune_ms": tail_ms, "seed": b.seed,
                    "distinct_kv_caches": st["n_caches"], "kv_cache_bytes": st["kv_bytes"]},
-        "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel (verify_attention, one launch per layer call)",
+        "roofline": {"bound": "hbm", "kernel": f"{attn_kernel} (verify_attention, one launch per layer call"
+                                               + ("" if args.no_plan else "; the step's one attn_plan_kernel launch is inside the figure") + ")",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(args.workload), "algorithmic_bytes_per_launch": attn_bytes,
+                     "traffic": traffic, "traffic_source": traffic_src, "algorithmic_bytes_per_launch": attn_bytes,
                      "launch_us": attn_ms * 1e3},
+        "kernels": kernel_figures(b, st, call_us),
     }
     if args.overlap > 0:
         result["overlap"] = overlap_measure(fsr, torch, workloads, b, args.layers, args.overlap)

@@ -66,9 +66,10 @@ class ChunkedVerifier:
             self.plan = B_.attn_plan(self.q_chunk, k0, block_tables, ctx_lens, cu_q, scale=scale, out_dtype=self.out.dtype,
                                      max_q_len=chunk_S_max + 1)
 
-    def run(self, after_chunk: Optional[Callable[[int, "ChunkedVerifier"], None]] = None):
-        """Enqueue the whole step on the current stream.  ``after_chunk(k, self)`` (eager runs only) is called
-        behind chunk k's launches, e.g. to record events or to look at the chunk's row selection."""
+    def run(self, mark: Optional[Callable[[str, int, "ChunkedVerifier"], None]] = None):
+        """Enqueue the whole step on the current stream.  ``mark(stage, k, self)`` (eager runs only) is called
+        at "attn_begin" / "attn_end" (around chunk k's attention launches) and "chunk_end", e.g. to record events
+        or to look at the chunk's row selection."""
         a = self.a
         Bn = self.Bn
         B_.frontier_init(a["spec_lens"], self.pos, self.active, self.n_out, self.acc_total, self.out_tokens)
@@ -81,10 +82,14 @@ class ChunkedVerifier:
             if self.plan is not None:
                 B_.attn_plan(self.q_chunk, a["k_caches"][0], a["block_tables"], self.chunk_ctx, tsel["new_cu_q"],
                              scale=a["scale"], out_dtype=self.out.dtype, max_q_len=self.chunk_S_max + 1, plan=self.plan)
+            if mark is not None:
+                mark("attn_begin", k, self)
             for k_cache, v_cache in zip(a["k_caches"], a["v_caches"]):
                 B_.verify_attention(self.q_chunk, k_cache, v_cache, a["block_tables"], self.chunk_ctx, None, tsel["new_cu_q"],
                                     scale=a["scale"], out=self.o_chunk, workspace=self.ws_attn,
                                     max_q_len=self.chunk_S_max + 1, plan=self.plan)
+            if mark is not None:
+                mark("attn_end", k, self)
             # the chunk's rows go back to their original positions; rows of other chunks keep their values
             B_.prune_scatter(self.o_chunk, tsel["src_row"], tsel["new_cu_q"][Bn:], self.out)
             B_.spec_accept(a["p_target"], a["p_draft"], a["draft_tokens"], a["u_accept"], a["u_sample"], tsel["new_cu_q"],
@@ -93,8 +98,8 @@ class ChunkedVerifier:
                            accepted_len=self.acc, n_emitted=self.nem, emitted=self.em, workspace=self.ws_acc)
             B_.frontier_commit(a["spec_lens"], chunk_len, self.acc, self.nem, self.em, self.pos, self.active, self.n_out,
                                self.acc_total, self.out_tokens)
-            if after_chunk is not None:
-                after_chunk(k, self)
+            if mark is not None:
+                mark("chunk_end", k, self)
         return dict(accepted_len=self.acc_total, n_emitted=self.n_out, emitted=self.out_tokens, out=self.out)
 
 
@@ -111,6 +116,6 @@ def verify_chunked(*, q, k_caches, v_caches, block_tables, ctx_lens, spec_lens, 
                         mode=mode, temperature=temperature, out=out, S_total_max=S_total_max, chunk_S_max=chunk_S_max,
                         use_plan=use_plan)
     rows = []
-    res = v.run(after_chunk=lambda k, s: rows.append(s.tsel["new_cu_q"][-1:].clone()))
+    res = v.run(mark=lambda stage, k, s: rows.append(s.tsel["new_cu_q"][-1:].clone()) if stage == "chunk_end" else None)
     res["rows"] = rows
     return res
