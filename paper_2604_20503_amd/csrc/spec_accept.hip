@@ -31,6 +31,7 @@ namespace {
 constexpr int kChunk = 4096;        // vocabulary tokens per chunk
 constexpr int kThreads = 256;       // threads per block in stats / partials / select
 constexpr int kPerThread = kChunk / kThreads;  // 16 contiguous tokens per thread in select
+constexpr int kMaxChunksLds = 256;  // chunk masses of a request that the selecting workgroup keeps in LDS (vocabularies up to 2^20)
 
 enum : int { kCaseNone = 0, kCaseResidual = 1, kCaseTarget = 2 };
 
@@ -343,6 +344,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     __shared__ int s_i[kThreads / 64];
     __shared__ double s_base, s_thr;
     __shared__ int s_chunk, s_fallback, s_last;
+    __shared__ double s_mass[2 * kMaxChunksLds];
     const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
@@ -376,27 +378,38 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
         if (!s_last) return;
     }
 
-    // ---- 3. the request's last workgroup draws the token: total mass and the chunk that holds u * R
-    // (sequential fp64 prefix over <= a few dozen chunks)
+    // ---- 3. the request's last workgroup draws the token: total mass and the chunk that holds u * R.
+    // The chunk masses come from memory (other workgroups wrote them): all threads fetch them together
+    // into LDS, then one thread runs the sequential fp64 prefix over the <= a few dozen chunks.
+    double* l_res = reinterpret_cast<double*>(s_mass);
+    double* l_tgt = l_res + kMaxChunksLds;
+    const bool in_lds = nc <= kMaxChunksLds;
+    if (in_lds) {
+        for (int cc = threadIdx.x; cc < nc; cc += kThreads) {
+            l_res[cc] = fetch_f64(ws.mass_res + (size_t)i * nc + cc);
+            l_tgt[cc] = fetch_f64(ws.mass_tgt + (size_t)i * nc + cc);
+        }
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        const double* mres = ws.mass_res + (size_t)i * nc;
-        const double* mtgt = ws.mass_tgt + (size_t)i * nc;
+        const double* gres = ws.mass_res + (size_t)i * nc;
+        const double* gtgt = ws.mass_tgt + (size_t)i * nc;
+        auto mres = [&](int cc) { return in_lds ? l_res[cc] : fetch_f64(gres + cc); };
+        auto mtgt = [&](int cc) { return in_lds ? l_tgt[cc] : fetch_f64(gtgt + cc); };
         double R = 0.0;
-        for (int cc = 0; cc < nc; ++cc) R += fetch_f64(mres + cc);
+        for (int cc = 0; cc < nc; ++cc) R += mres(cc);
         int fallback = 0;
-        const double* mass = mres;
         if (!(R > 0.0)) {  // residual is all zero: sample from the target row itself
             fallback = 1;
-            mass = mtgt;
             R = 0.0;
-            for (int cc = 0; cc < nc; ++cc) R += fetch_f64(mtgt + cc);
+            for (int cc = 0; cc < nc; ++cc) R += mtgt(cc);
         }
         const double thr = (double)u_sample[i] * R;
         double acc = 0.0, base = 0.0;
         int chunk = -1, last_pos = 0;
         double last_base = 0.0;
         for (int cc = 0; cc < nc; ++cc) {
-            const double prev = acc, mc = fetch_f64(mass + cc);
+            const double prev = acc, mc = fallback ? mtgt(cc) : mres(cc);
             acc += mc;
             if (mc > 0.0) {
                 last_pos = cc;
