@@ -277,6 +277,7 @@ struct KVStream {
     gmem_char* k_head;   // caches offset to the KV head
     gmem_char* v_head;
     int kb0, nw, kv_total, kend;
+    int kbeg;  // first key of the segment (tile_a * kTile): what a wave without tiles of its own reads as filler
 };
 
 constexpr int kStep = kWaves * kTile;
@@ -331,6 +332,7 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     // keys any row of this group may see
     st.kend = min(min(__builtin_amdgcn_readfirstlane(sg.tile_e) * kTile,
                       c + __builtin_amdgcn_readfirstlane(sg.j0) + __builtin_amdgcn_readfirstlane(sg.rows_g)), st.kv_total);
+    st.kbeg = kbeg;
     st.kb0 = kbeg + w * kTile;
     st.nw = st.kb0 < st.kend ? (st.kend - st.kb0 + kStep - 1) / kStep : 0;
     return st;
@@ -418,18 +420,18 @@ struct ShareWalker {
 // Issue the global loads of the wave's tile ti (no waiting); bt = the table in which the tile's pages
 // are looked up.  Tiles past the wave's last one are "issued" too, so that the number of loads in
 // flight is the same on every path and the compiler's wait counts stay exact: all their lanes read
-// the first bytes of the last tile (16 cache lines, already resident) and nothing consumes them.
-// Needs st.nw > 0.
+// the first bytes of the last tile (16 cache lines, already resident) and nothing consumes them; a
+// wave that has no tile of the segment reads the first bytes of the segment's first tile.
 template <bool TM, bool KV8>
 __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv, const const_i32* bt, typename TileOf<KV8>::type& t,
                                            int ti) {
     const int lane = threadIdx.x & 63, lg = lane >> 4, li = lane & 15;
     KVStream st;
     st.bt = uniform(bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
-    st.kb0 = uniform(sv.kb0); st.nw = uniform(sv.nw); st.kv_total = uniform(sv.kv_total);
+    st.kb0 = uniform(sv.kb0); st.nw = uniform(sv.nw); st.kv_total = uniform(sv.kv_total); st.kbeg = uniform(sv.kbeg);
     ti = uniform(ti);
     const bool real = ti < st.nw;
-    const int kb = st.kb0 + min(ti, st.nw - 1) * kStep;
+    const int kb = st.nw > 0 ? st.kb0 + min(ti, st.nw - 1) * kStep : st.kbeg;
     // per-lane byte offsets inside a (page, head) block: every load is then
     // "uniform base + this offset + immediate", with no per-load address arithmetic
     const int ks = key_stride<TM, KV8>(a);
@@ -509,20 +511,17 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     int v8_off[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) v8_off[r] = KV8 ? vtile_off(8 * r + (lane >> 3), 2 * (lane & 7)) : 0;
-    // The K/V stream does not depend on Q: start it before anything else of the segment.
     // Two tiles in flight per wave.  (A third, where the registers would allow it, does not raise
     // the rate: a compute unit draws only about twice its even share of the HBM bandwidth however
     // much it keeps in flight.)
     constexpr int kDepth = 2;
-    Tile ta, tb;
-    if (nw > 0) {
-        issue_tile<TM, KV8>(a, st, st.bt_first, ta, 0);
-        issue_tile<TM, KV8>(a, st, st.bt_first, tb, 1);
-    }
-
     // ---- Q^T operands: lane holds query row (mt*16 + li), d = 32 kk + 8 lg .. +7.  They are the
     // same for the 4 waves and for every tile, so they live in LDS ([mt*4 + kk][lane] x 16 bytes,
     // read back lane-contiguous) instead of 16 registers per query tile.
+    // Their loads go out BEFORE the K/V tiles': vector loads return in issue order, so query rows
+    // sent for behind 32 KB of tiles would arrive only after the second tile, and every wave of the
+    // workgroup would sit at the barrier below until then; sent for first they are staged while the
+    // tiles travel, and the first tile is worked on as soon as it lands.
     char* qbuf = smem + kQOff;
     int lim[MT];
 #pragma unroll
@@ -530,18 +529,33 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         const int m = mt * 16 + li;
         lim[mt] = m < M_g ? c + j0 + m / G : -1;
     }
-    for (int pr = w; pr < MT * 4; pr += kWaves) {
+    constexpr int kQPer = (MT * 4 + kWaves - 1) / kWaves;  // pieces of the operand buffer this wave brings in
+    s16x8 q_piece[kQPer];
+#pragma unroll
+    for (int r = 0; r < kQPer; ++r) {
+        const int pr = w + r * kWaves;
         const int mt = pr >> 2, kk = pr & 3;
         const int m = mt * 16 + li;
-        const bool ok = m < M_g;
+        const bool ok = m < M_g && pr < MT * 4;
         const int j = j0 + m / G, gq = m % G;
         // the contraction index of matrix instruction kk, lane group lg covers d = 32 kk + 8 lg .. +7 with bf16
         // caches; with 8-bit ones a lane's 16-byte K chunk holds d = 64 c + 16 lg .. +15, split over kk = 2c, 2c+1
         const int d_off = KV8 ? 64 * (kk >> 1) + 16 * lg + 8 * (kk & 1) : 8 * lg + 32 * kk;
         const uint16_t* qp = a.q + ((size_t)(q0 + (ok ? j : j0)) * a.H_q + kvh * G + (ok ? gq : 0)) * kD + d_off;
-        s16x8 t = *reinterpret_cast<const s16x8*>(qp);
-        if (!ok) t = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        *reinterpret_cast<s16x8*>(qbuf + (pr * 64 + lane) * 16) = t;
+        q_piece[r] = *reinterpret_cast<const s16x8*>(qp);
+        if (!ok) q_piece[r] = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // (issued by every wave, also one without a tile of this segment: with no branch around them the
+    // compiler's wait for the query rows counts exactly the loads behind them)
+    Tile ta, tb;
+    issue_tile<TM, KV8>(a, st, st.bt_first, ta, 0);
+    issue_tile<TM, KV8>(a, st, st.bt_first, tb, 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < kQPer; ++r) {
+        const int pr = w + r * kWaves;
+        if (pr < MT * 4) *reinterpret_cast<s16x8*>(qbuf + (pr * 64 + lane) * 16) = q_piece[r];
     }
     __syncthreads();
 
