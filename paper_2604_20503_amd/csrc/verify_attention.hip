@@ -740,15 +740,19 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     bool redo = false;
     if (nw > 0) {
         f32x4 s[MT][2];
-        // one tile: wait for it, stage V, scores; refill its registers with the tile kDepth
-        // further on (past the end: a harmless repeat of the last tile); softmax and P V
+        // one tile: wait for it, stage V, scores; softmax and P V; then refill its registers with the
+        // tile kDepth further on (past the end: a harmless repeat of the last tile).  The refill goes out
+        // after the tile's arithmetic, not before it: HBM is saturated either way, and the fewer bytes the
+        // chip keeps queued the sooner a segment's first tiles, its partials and its arrival count come back
+        // (measured: 0.2 to 0.7 % per launch on every workload shape).
         auto fast_tile = [&](Tile& tl, int t) {
             const bool real = t < nw;
             if (real) stage_and_scores(tl, kb0 + t * kStep, s);
             __builtin_amdgcn_sched_barrier(0);
+            if (real) fast_softmax_pv(kb0 + t * kStep, s);
+            __builtin_amdgcn_sched_barrier(0);
             issue(tl, t + kDepth);
             __builtin_amdgcn_sched_barrier(0);
-            if (real) fast_softmax_pv(kb0 + t * kStep, s);
         };
         for (int t = 0; t < nw; t += kDepth) {
             fast_tile(ta, t);
