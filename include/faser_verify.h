@@ -157,7 +157,7 @@ int fsr_verify_attention(const void* q, const void* k_cache, const void* v_cache
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
  * minus spec_lens and the workspace; same kernels, same results.  The partial results and arrival
  * counters that the workspace would hold live in a buffer built into the library
- * (fsr_static_scratch_bytes() bytes, about 17 MB, resident on every GPU the library runs on until the
+ * (fsr_static_scratch_bytes() bytes, about 26 MB, resident on every GPU the library runs on until the
  * process ends), laid out for a grid of at most 256 workgroups.  The call allocates and frees nothing.
  * Shapes whose scratch would not fit return FSR_EWS before anything is launched.  All calls on one
  * GPU share that buffer: calls that can overlap in time on one GPU (different streams) race; on one

@@ -65,12 +65,14 @@ constexpr int kVTileBytes = kTile * kD * 2;
 constexpr int kRedBytes = kWaves * 16 * kRedStride * 4;
 constexpr int kMlBytes = 2 * kWaves * 16 * kMaxMT * 4;
 constexpr int kQBytes = kMaxMT * 4 * 64 * 16;
-template <int RT>
+constexpr int kWideMT = 3;  // query tiles per team of a two-team segment (see attend_segment)
+constexpr int kQTeamBytes = kWideMT * 4 * 64 * 16;
+template <int RT, bool WIDE>
 struct Lds {
     static constexpr int kStage = kWaves * kVTileBytes > RT * kRedBytes ? kWaves * kVTileBytes : RT * kRedBytes;
     static constexpr int kMl = kStage;
-    static constexpr int kQ = kMl + kMlBytes;  // Q^T operands of the current item: [kMaxMT * 4][64 lanes][16 B]
-    static constexpr int kFixed = kQ + kQBytes;
+    static constexpr int kQ = kMl + kMlBytes;  // Q^T operands of the current item: [query tile * 4][64 lanes][16 B], per team
+    static constexpr int kFixed = kQ + (WIDE ? 2 * kQTeamBytes : kQBytes);
 };
 // The kernel that reads a plan has the LDS to itself and merges all query tiles of a segment at once.  The
 // kernel that builds its own schedule keeps three tables sized from the call's B behind the fixed part --
@@ -78,15 +80,16 @@ struct Lds {
 // lengths the prefix has loaded anyway (the walker reads them there) -- and merges two tiles at a time,
 // which still fits 160 KB at B = 4096.
 constexpr int kStreamRT = 2;
-constexpr int kFixedSmem = Lds<kStreamRT>::kFixed;
-__host__ __device__ constexpr int planned_smem(int mt_max) {
-    return mt_max <= 1 ? Lds<1>::kFixed : mt_max == 2 ? Lds<2>::kFixed : mt_max == 3 ? Lds<3>::kFixed : Lds<4>::kFixed;
+__host__ __device__ constexpr int stream_fixed_smem(bool wide) { return wide ? Lds<kStreamRT, true>::kFixed : Lds<kStreamRT, false>::kFixed; }
+__host__ __device__ constexpr int planned_smem(int mt_max, bool wide) {
+    return wide ? Lds<kWideMT, true>::kFixed
+                : mt_max <= 1 ? Lds<1, false>::kFixed : mt_max == 2 ? Lds<2, false>::kFixed : mt_max == 3 ? Lds<3, false>::kFixed : Lds<4, false>::kFixed;
 }
-__host__ __device__ constexpr int pref_off() { return kFixedSmem; }
-__host__ __device__ constexpr int scan_off(int B) { return pref_off() + ((B + 1) * 8 + 15) / 16 * 16; }
+// the schedule tables, as offsets from where they start
+__host__ __device__ constexpr int scan_off(int B) { return ((B + 1) * 8 + 15) / 16 * 16; }
 __host__ __device__ constexpr int cu_off(int B) { return scan_off(B) + 64; }
 __host__ __device__ constexpr int ctx_off(int B) { return cu_off(B) + (B + 4) * 4; }
-__host__ __device__ constexpr int sched_smem(int B) { return ctx_off(B) + (B + 4) * 4; }
+__host__ __device__ constexpr int tables_bytes(int B) { return ctx_off(B) + (B + 4) * 4; }
 // Measured: a tile takes 2.0 / 2.4 / 2.5 us per wave with 1 / 2 / 3 query tiles riding on it (bandwidth, not the
 // matrix work, sets the pace), and taking up an item costs a workgroup 6 to 10 us of merge, count and refill.
 // Swept on four batches of the 16-request shape and on the 128- and 512-request shapes: base 3..6 with 12..20
@@ -118,7 +121,8 @@ struct FastArgs {
     uint32_t plan_key;             // what the plan must have been built for (planned kernel only)
     int B, H_q, H_kv, G, max_pages, n_pages;
     int nb;          // workgroups of the persistent grid
-    int m_cap;       // rows (G * q_len) a partial slot holds = 16 * MTMAX
+    int m_cap;       // rows (G * positions of a row group) a partial slot holds
+    int wide;        // row groups hold two teams' worth of suffix positions (see attend_segment)
     int out_bf16;
     float scale_log2;
     const float* k_scale;  // 8-bit caches: per KV head, cached key = decode(byte) * k_scale[head]; else unused
@@ -163,17 +167,20 @@ struct Group {
 };
 
 // Group of request (context c, q_len rows) that starts at suffix position j0.
+// Suffix positions whose G * positions query rows fit mt_max query tiles: what one team of waves takes.
+__device__ __forceinline__ int rows_per_team(const FastArgs& a, int mt_max) { return max((16 * mt_max) / a.G, 1); }
+__device__ __forceinline__ int rows_per_group(const FastArgs& a, int mt_max) { return rows_per_team(a, mt_max) * (a.wide ? 2 : 1); }
 __device__ __forceinline__ Group group_at(const FastArgs& a, int mt_max, int c, int q_len, int j0) {
-    const int per_group = max((16 * mt_max) / a.G, 1);
+    const int per_team = rows_per_team(a, mt_max);
     Group gr;
     gr.j0 = j0;
-    gr.rows_g = min(per_group, q_len - j0);
+    gr.rows_g = min(rows_per_group(a, mt_max), q_len - j0);
     const int visible = min(c + j0 + gr.rows_g, a.max_pages * kP);  // keys the group's last row sees
     gr.nt = (visible + kTile - 1) / kTile + a.seg_tiles;
-    gr.cost = a.cost_base + min((a.G * gr.rows_g + 15) >> 4, mt_max);
+    const int rows_a = min(gr.rows_g, per_team), rows_b = gr.rows_g - rows_a;
+    gr.cost = a.cost_base + min((a.G * rows_a + 15) >> 4, mt_max) + ((a.G * rows_b + 15) >> 4);
     return gr;
 }
-__device__ __forceinline__ int rows_per_group(const FastArgs& a, int mt_max) { return max((16 * mt_max) / a.G, 1); }
 
 // Returns the largest per-tile cost of any item.
 __device__ int build_cost_prefix(const FastArgs& a, int mt_max, long long* pref, long long* scratch, int* lds_cu, int* lds_ctx) {
@@ -290,9 +297,10 @@ struct KVStream {
     gmem_char* v_head;
     int kb0, nw, kv_total, kend;
     int kbeg;  // first key of the segment (tile_a * kTile): what a wave without tiles of its own reads as filler
+    int step;  // keys from one tile of the wave to its next: 32 x the waves that share the segment's keys
+    // the wave's team: its suffix positions j0_t .. j0_t + rows_t - 1; per_team = positions of a full team
+    int team, j0_t, rows_t, per_team;
 };
-
-constexpr int kStep = kWaves * kTile;
 
 // Values that are the same in every lane, moved to scalar registers: addresses built from them
 // are scalar, and loads through them (the page look-ups) are scalar loads that never wait on the
@@ -329,9 +337,12 @@ __device__ __forceinline__ int key_stride(const FastArgs& a) { return (TM ? a.H_
 template <bool TM, bool KV8>
 __device__ __forceinline__ int head_stride() { return (TM ? kD : kP * kD) * (KV8 ? 1 : 2); }
 
+// teams = 1: the 4 waves split the segment's keys.  teams = 2: waves 0, 1 take the first per_team
+// positions of the row group and waves 2, 3 the rest; the two waves of a team split the keys.
 template <bool TM, bool KV8>
-__device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment& sg) {
+__device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment& sg, int per_team, int teams) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wpt = kWaves / teams, team = w / wpt, wk = w % wpt;
     KVStream st;
     st.bt = (const const_i32*)(a.bt + (size_t)__builtin_amdgcn_readfirstlane(sg.i) * a.max_pages);
     st.rec_pages = false;
@@ -342,12 +353,17 @@ __device__ __forceinline__ KVStream make_stream(const FastArgs& a, const Segment
     const int c = __builtin_amdgcn_readfirstlane(sg.c), q_len = __builtin_amdgcn_readfirstlane(sg.q_len);
     st.kv_total = min(c + q_len, a.max_pages * kP);  // tokens of this request in the cache
     const int kbeg = __builtin_amdgcn_readfirstlane(sg.tile_a) * kTile;
-    // keys any row of this group may see
-    st.kend = min(min(__builtin_amdgcn_readfirstlane(sg.tile_e) * kTile,
-                      c + __builtin_amdgcn_readfirstlane(sg.j0) + __builtin_amdgcn_readfirstlane(sg.rows_g)), st.kv_total);
+    const int j0 = __builtin_amdgcn_readfirstlane(sg.j0), rows_g = __builtin_amdgcn_readfirstlane(sg.rows_g);
+    st.team = team;
+    st.per_team = per_team;
+    st.j0_t = j0 + team * per_team;
+    st.rows_t = teams == 1 ? rows_g : team == 0 ? min(rows_g, per_team) : rows_g - per_team;
+    // keys any row of the team may see
+    st.kend = min(min(__builtin_amdgcn_readfirstlane(sg.tile_e) * kTile, c + st.j0_t + st.rows_t), st.kv_total);
     st.kbeg = kbeg;
-    st.kb0 = kbeg + w * kTile;
-    st.nw = st.kb0 < st.kend ? (st.kend - st.kb0 + kStep - 1) / kStep : 0;
+    st.step = wpt * kTile;
+    st.kb0 = kbeg + wk * kTile;
+    st.nw = st.kb0 < st.kend ? (st.kend - st.kb0 + st.step - 1) / st.step : 0;
     return st;
 }
 
@@ -441,9 +457,10 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     KVStream st;
     st.bt = uniform(sv.bt); st.k_head = uniform(sv.k_head); st.v_head = uniform(sv.v_head);
     st.kb0 = uniform(sv.kb0); st.nw = uniform(sv.nw); st.kv_total = uniform(sv.kv_total); st.kbeg = uniform(sv.kbeg);
+    st.step = uniform(sv.step);
     ti = uniform(ti);
     const bool real = ti < st.nw;
-    const int kb = st.nw > 0 ? st.kb0 + min(ti, st.nw - 1) * kStep : st.kbeg;
+    const int kb = st.nw > 0 ? st.kb0 + min(ti, st.nw - 1) * st.step : st.kbeg;
     // per-lane byte offsets inside a (page, head) block: every load is then
     // "uniform base + this offset + immediate", with no per-load address arithmetic
     const int ks = key_stride<TM, KV8>(a);
@@ -452,7 +469,7 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     if (FIRST && sv.rec_pages) {
         // from the plan record (already clamped to the pool and to the request's last page): no look-up
         // stands between reading the record and sending for the tiles
-        const int idx = uniform((kb - st.kbeg) >> 4);  // 2 w + 8 ti <= 14
+        const int idx = uniform((kb - st.kbeg) >> 4);  // at most 2 * 3 + 8 = 14
         pg0 = __builtin_amdgcn_readlane(sv.pgv, idx);
         pg1 = __builtin_amdgcn_readlane(sv.pgv, idx + 1);
     } else {
@@ -495,23 +512,32 @@ __device__ __forceinline__ void issue_tile(const FastArgs& a, const KVStream& sv
     }
 }
 
-// Process one segment: stream the wave's tiles, merge the 4 waves, write the result or the partial.
-template <int MT, bool TM, bool KV8, int RT>
+// Process one segment: stream the wave's tiles, merge the waves, write the result or the partial.
+// TEAMS = 1: the 4 waves split the keys and all work on the same (up to MT x 16) query rows.
+// TEAMS = 2, for row groups wider than that: waves 0, 1 take the first per_team suffix positions and
+// waves 2, 3 the rest, each pair splitting the keys between its two waves.  Both pairs read the same
+// K/V bytes at about the same time, so HBM delivers them once (the second read is served by the L2
+// of the workgroup's die) where two passes over the item would stream them twice.
+template <int MT, bool TM, bool KV8, int RT, int TEAMS>
 __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem) {
+    constexpr int kWPT = kWaves / TEAMS;  // waves that split the keys
+    typedef Lds<RT, TEAMS == 2> L;
     // everything that is the same for the whole wave goes to scalar registers
     const int kvh = __builtin_amdgcn_readfirstlane(sg.kvh);
     const int c = __builtin_amdgcn_readfirstlane(sg.c);
     const int q0 = __builtin_amdgcn_readfirstlane(sg.q0);
-    const int j0 = __builtin_amdgcn_readfirstlane(sg.j0);
-    const int rows_g = __builtin_amdgcn_readfirstlane(sg.rows_g);
+    const int team = uniform(st.team), per_team = uniform(st.per_team);
+    const int j0 = uniform(st.j0_t);        // the team's positions
+    const int rows_g = uniform(st.rows_t);
     const bool final_out = sg.final_out;
     const int slot = sg.slot;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wk = w % kWPT;
     const int lg = lane >> 4, li = lane & 15;
     const int G = a.G;
     const int M_g = G * rows_g;
-    const int kv_total = uniform(st.kv_total), kb0 = uniform(st.kb0), nw = uniform(st.nw);
+    const int kv_total = uniform(st.kv_total), kb0 = uniform(st.kb0), nw = uniform(st.nw), step = uniform(st.step);
     char* vbuf = smem + w * kVTileBytes;
 
     const int vw_even = vtile_off(lg, li), vw_odd = vtile_off(4 + lg, li) - 4 * 256;  // LDS store offsets (+ 1024 r)
@@ -543,18 +569,18 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     // sent for behind 32 KB of tiles would arrive only after the second tile, and every wave of the
     // workgroup would sit at the barrier below until then; sent for first they are staged while the
     // tiles travel, and the first tile is worked on as soon as it lands.
-    char* qbuf = smem + Lds<RT>::kQ;
+    char* qbuf = smem + L::kQ + (TEAMS == 2 ? team * kQTeamBytes : 0);
     int lim[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + li;
         lim[mt] = m < M_g ? c + j0 + m / G : -1;
     }
-    constexpr int kQPer = (MT * 4 + kWaves - 1) / kWaves;  // pieces of the operand buffer this wave brings in
+    constexpr int kQPer = (MT * 4 + kWPT - 1) / kWPT;  // pieces of the team's operand buffer this wave brings in
     s16x8 q_piece[kQPer];
 #pragma unroll
     for (int r = 0; r < kQPer; ++r) {
-        const int pr = w + r * kWaves;
+        const int pr = wk + r * kWPT;
         const int mt = pr >> 2, kk = pr & 3;
         const int m = mt * 16 + li;
         const bool ok = m < M_g && pr < MT * 4;
@@ -575,7 +601,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < kQPer; ++r) {
-        const int pr = w + r * kWaves;
+        const int pr = wk + r * kWPT;
         if (pr < MT * 4) *reinterpret_cast<s16x8*>(qbuf + (pr * 64 + lane) * 16) = q_piece[r];
     }
     __syncthreads();
@@ -768,9 +794,9 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         // (measured: 0.2 to 0.7 % per launch on every workload shape).
         auto fast_tile = [&](Tile& tl, int t) {
             const bool real = t < nw;
-            if (real) stage_and_scores(tl, kb0 + t * kStep, s);
+            if (real) stage_and_scores(tl, kb0 + t * step, s);
             __builtin_amdgcn_sched_barrier(0);
-            if (real) fast_softmax_pv(kb0 + t * kStep, s);
+            if (real) fast_softmax_pv(kb0 + t * step, s);
             __builtin_amdgcn_sched_barrier(0);
             issue(tl, t + kDepth);
             __builtin_amdgcn_sched_barrier(0);
@@ -832,16 +858,16 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         issue_one(ta, 1);
         bool more = true;
         while (more) {
-            raise_refs(kb0 + t * kStep, s);
+            raise_refs(kb0 + t * step, s);
             for (;;) {
-                exact_softmax_pv(kb0 + t * kStep, s);
+                exact_softmax_pv(kb0 + t * step, s);
                 if (++t >= nw) {
                     more = false;
                     break;
                 }
-                stage_and_scores(ta, kb0 + t * kStep, s);
+                stage_and_scores(ta, kb0 + t * step, s);
                 issue_one(ta, t + 1);
-                if (needs_raise(kb0 + t * kStep, s)) break;
+                if (needs_raise(kb0 + t * step, s)) break;
             }
         }
     }
@@ -853,8 +879,8 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         l_run[mt] += __shfl_xor(l_run[mt], 32, 64);
     }
 
-    // ---- merge the 4 waves (each saw a disjoint set of keys)
-    float* red_m = reinterpret_cast<float*>(smem + Lds<RT>::kMl);  // [kWaves][16 * kMaxMT]
+    // ---- merge the waves of each team (each saw a disjoint set of keys)
+    float* red_m = reinterpret_cast<float*>(smem + L::kMl);  // [kWaves][16 * kMaxMT]
     float* red_l = red_m + kWaves * 16 * kMaxMT;
     float* red_o = reinterpret_cast<float*>(smem);  // [query tile of the batch][kWaves][16][kRedStride], shares the V tiles' space
     const __amdgpu_buffer_rsrc_t buf_o = partial_buffer(a.part_o), buf_ml = partial_buffer(a.part_ml);
@@ -868,6 +894,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
     __syncthreads();
     constexpr int kRedFloats = kWaves * 16 * kRedStride;  // one query tile of all waves in the merge buffer
+    const int w0 = team * kWPT;  // first wave of this wave's team
 #pragma unroll
     for (int mt0 = 0; mt0 < MT; mt0 += RT) {
 #pragma unroll
@@ -876,7 +903,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             if (mt >= MT) break;
             float m_star = -INFINITY;
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) m_star = fmaxf(m_star, red_m[ww * 16 * kMaxMT + mt * 16 + li]);
+            for (int ww = 0; ww < kWPT; ++ww) m_star = fmaxf(m_star, red_m[(w0 + ww) * 16 * kMaxMT + mt * 16 + li]);
             const float m_use = m_star == -INFINITY ? 0.0f : m_star;
             const float f = fast_exp2(m_run[mt] - m_use) * v_mul;
 #pragma unroll
@@ -886,67 +913,75 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             }
         }
         __syncthreads();
-        // 256 threads sum 16 rows x 128 d over the 4 waves: thread -> row tid/16, 8 consecutive d
+        // 256 threads sum 16 rows x 128 d over the waves of a team: thread -> row tid/16, 8 consecutive d
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            const int mt = mt0 + r;
-            if (mt >= MT) break;
-            const float* red_t = red_o + r * kRedFloats;
-            const int row = threadIdx.x >> 4, d0 = (threadIdx.x & 15) * 8;
-            const int m = mt * 16 + row;
-            // every LDS read of the tile is sent for before the first sum: one wait instead of one per pair
-            // of reads (a wave runs alone on its SIMD, nothing else hides the LDS latency)
-            f32x4 part0[kWaves], part1[kWaves];
-            float wm[kWaves], wl[kWaves];
+        for (int tt = 0; tt < TEAMS; ++tt) {
+            // the rows of team tt (every thread sums for both teams, whichever its own wave belongs to)
+            const int j0_s = TEAMS == 1 ? j0 : uniform(sg.j0) + tt * per_team;
+            const int rows_s = TEAMS == 1 ? rows_g : tt == 0 ? min(uniform(sg.rows_g), per_team) : uniform(sg.rows_g) - per_team;
+            const int M_s = G * rows_s, ws0 = tt * kWPT;
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                part0[ww] = *reinterpret_cast<const f32x4*>(red_t + (ww * 16 + row) * kRedStride + d0);
-                part1[ww] = *reinterpret_cast<const f32x4*>(red_t + (ww * 16 + row) * kRedStride + d0 + 4);
-                wm[ww] = red_m[ww * 16 * kMaxMT + m];
-                wl[ww] = red_l[ww * 16 * kMaxMT + m];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            f32x4 s0 = part0[0], s1 = part1[0];
+            for (int r = 0; r < RT; ++r) {
+                const int mt = mt0 + r;
+                if (mt >= MT) break;
+                const float* red_t = red_o + r * kRedFloats;
+                const int row = threadIdx.x >> 4, d0 = (threadIdx.x & 15) * 8;
+                const int m = mt * 16 + row;
+                // every LDS read of the tile is sent for before the first sum: one wait instead of one per pair
+                // of reads (a wave runs alone on its SIMD, nothing else hides the LDS latency)
+                f32x4 part0[kWPT], part1[kWPT];
+                float wm[kWPT], wl[kWPT];
 #pragma unroll
-            for (int ww = 1; ww < kWaves; ++ww) {
-                s0 += part0[ww];
-                s1 += part1[ww];
-            }
-            if (m < M_g) {
-                float ms = -INFINITY;
+                for (int ww = 0; ww < kWPT; ++ww) {
+                    part0[ww] = *reinterpret_cast<const f32x4*>(red_t + ((ws0 + ww) * 16 + row) * kRedStride + d0);
+                    part1[ww] = *reinterpret_cast<const f32x4*>(red_t + ((ws0 + ww) * 16 + row) * kRedStride + d0 + 4);
+                    wm[ww] = red_m[(ws0 + ww) * 16 * kMaxMT + m];
+                    wl[ww] = red_l[(ws0 + ww) * 16 * kMaxMT + m];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                f32x4 s0 = part0[0], s1 = part1[0];
 #pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) ms = fmaxf(ms, wm[ww]);
-                const float mu = ms == -INFINITY ? 0.0f : ms;
-                float ls = 0.0f;
+                for (int ww = 1; ww < kWPT; ++ww) {
+                    s0 += part0[ww];
+                    s1 += part1[ww];
+                }
+                if (m < M_s) {
+                    float ms = -INFINITY;
 #pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) ls += wl[ww] * fast_exp2(wm[ww] - mu);
-                if (final_out) {
-                    const int j = j0 + m / G, h = kvh * G + m % G;
-                    const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
-                    const float inv = 1.0f / ls;
-                    s0 *= inv;
-                    s1 *= inv;
-                    if (a.out_bf16) {
-                        s16x8 pk;
+                    for (int ww = 0; ww < kWPT; ++ww) ms = fmaxf(ms, wm[ww]);
+                    const float mu = ms == -INFINITY ? 0.0f : ms;
+                    float ls = 0.0f;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            pk[e] = (short)f32_to_bf16_rne(s0[e]);
-                            pk[4 + e] = (short)f32_to_bf16_rne(s1[e]);
+                    for (int ww = 0; ww < kWPT; ++ww) ls += wl[ww] * fast_exp2(wm[ww] - mu);
+                    if (final_out) {
+                        const int j = j0_s + m / G, h = kvh * G + m % G;
+                        const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
+                        const float inv = 1.0f / ls;
+                        s0 *= inv;
+                        s1 *= inv;
+                        if (a.out_bf16) {
+                            s16x8 pk;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                pk[e] = (short)f32_to_bf16_rne(s0[e]);
+                                pk[4 + e] = (short)f32_to_bf16_rne(s1[e]);
+                            }
+                            *reinterpret_cast<s16x8*>(reinterpret_cast<uint16_t*>(a.out) + o_idx) = pk;
+                        } else {
+                            float* dst = reinterpret_cast<float*>(a.out) + o_idx;
+                            *reinterpret_cast<f32x4*>(dst) = s0;
+                            *reinterpret_cast<f32x4*>(dst + 4) = s1;
                         }
-                        *reinterpret_cast<s16x8*>(reinterpret_cast<uint16_t*>(a.out) + o_idx) = pk;
+                        if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (ms + __log2f(ls)) * kLn2;
                     } else {
-                        float* dst = reinterpret_cast<float*>(a.out) + o_idx;
-                        *reinterpret_cast<f32x4*>(dst) = s0;
-                        *reinterpret_cast<f32x4*>(dst + 4) = s1;
+                        // pieces are read by another workgroup of this launch, possibly on another die:
+                        // device-coherent stores (written through to memory) instead of a cache flush before the count.
+                        // A slot holds the row group's rows in order: the second team's behind the first's.
+                        const size_t prow = (size_t)slot * a.m_cap + tt * G * per_team + m;
+                        coherent_store4(buf_o, prow * kD + d0, s0);
+                        coherent_store4(buf_o, prow * kD + d0 + 4, s1);
+                        if (d0 == 0) coherent_store4(buf_ml, prow * 4, f32x4{ms, ls, __builtin_bit_cast(float, (uint32_t)a.call_id), 0.0f});
                     }
-                    if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (ms + __log2f(ls)) * kLn2;
-                } else {
-                    // pieces are read by another workgroup of this launch, possibly on another die:
-                    // device-coherent stores (written through to memory) instead of a cache flush before the count
-                    const size_t prow = (size_t)slot * a.m_cap + m;
-                    coherent_store4(buf_o, prow * kD + d0, s0);
-                    coherent_store4(buf_o, prow * kD + d0 + 4, s1);
-                    if (d0 == 0) coherent_store4(buf_ml, prow * 4, f32x4{ms, ls, __builtin_bit_cast(float, (uint32_t)a.call_id), 0.0f});
                 }
             }
         }
@@ -954,10 +989,25 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     }
 }
 
-template <int MTMAX, bool TM, bool KV8, int RT>
-__device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, const KVStream& st, char* smem) {
+// Stream, attend and merge one segment with the kernel variant its row group needs.
+template <int MTMAX, bool TM, bool KV8, int RT, bool WIDE>
+__device__ __forceinline__ void attend_dispatch(const FastArgs& a, const Segment& sg, char* smem, bool rec_pages, int pgv) {
+    const int per_team = rows_per_team(a, MTMAX);
+    if constexpr (WIDE) {
+        static_assert(MTMAX == kWideMT, "two-team segments are built for three query tiles per team");
+        if (sg.rows_g > per_team) {
+            KVStream st = make_stream<TM, KV8>(a, sg, per_team, 2);
+            st.rec_pages = rec_pages;
+            st.pgv = pgv;
+            attend_segment<MTMAX, TM, KV8, RT, 2>(a, sg, st, smem);
+            return;
+        }
+    }
+    KVStream st = make_stream<TM, KV8>(a, sg, per_team, 1);
+    st.rec_pages = rec_pages;
+    st.pgv = pgv;
     const int mt = (a.G * sg.rows_g + 15) >> 4;
-#define FSR_SEG(MT) attend_segment<MT, TM, KV8, RT>(a, sg, st, smem)
+#define FSR_SEG(MT) attend_segment<MT, TM, KV8, RT, 1>(a, sg, st, smem)
     if constexpr (MTMAX == 1) {
         FSR_SEG(1);
     } else if constexpr (MTMAX == 2) {
@@ -981,77 +1031,80 @@ __device__ void combine_cut_item(const FastArgs& a, int b_first, int b_last, int
     constexpr int kE = (16 * MTMAX * (kD / 4) + kThreads - 1) / kThreads;
     constexpr int kBatch = 2;
     const int n_elem = M * (kD / 4);
-    float m_star[kE], l[kE];
-    f32x4 o[kE];
-#pragma unroll
-    for (int e = 0; e < kE; ++e) {
-        m_star[e] = -INFINITY;
-        l[e] = 0.0f;
-        o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    for (int bb0 = b_first; bb0 <= b_last; bb0 += kBatch) {
-        float pm[kE][kBatch], pl[kE][kBatch];
-        f32x4 po[kE][kBatch];
+    // a row group of two teams holds up to twice 16 * MTMAX rows: a second round over the pieces
+    for (int e_base = 0; e_base < n_elem; e_base += kE * kThreads) {
+        float m_star[kE], l[kE];
+        f32x4 o[kE];
 #pragma unroll
         for (int e = 0; e < kE; ++e) {
-            const int idx = min((int)threadIdx.x + e * kThreads, n_elem - 1);  // past the end: a valid element, unused
+            m_star[e] = -INFINITY;
+            l[e] = 0.0f;
+            o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int bb0 = b_first; bb0 <= b_last; bb0 += kBatch) {
+            float pm[kE][kBatch], pl[kE][kBatch];
+            f32x4 po[kE][kBatch];
+#pragma unroll
+            for (int e = 0; e < kE; ++e) {
+                const int idx = min(e_base + (int)threadIdx.x + e * kThreads, n_elem - 1);  // past the end: a valid element, unused
+                const int m = idx / (kD / 4), d0 = (idx % (kD / 4)) * 4;
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int bb = min(bb0 + k, b_last);  // past the end: the last piece again, weighted 0 below
+                    const size_t row = (size_t)(bb * 2 + (bb == b_first ? 1 : 0)) * a.m_cap + m;
+                    // Ordinary loads are enough on this side (and 0.5 us quicker than device-coherent ones): a piece
+                    // was stored through to memory and acknowledged before it was counted; a slot is written once and
+                    // read once per launch, so neither this compute unit's L1 nor this die's L2 can hold an older copy
+                    // of it from this launch, and copies from earlier launches are dropped when a kernel starts (the same
+                    // rule that lets any kernel read what an earlier kernel wrote on another die).
+                    const f32x4 ml4 = *reinterpret_cast<const f32x4*>(a.part_ml + row * 4);
+                    // a slot that this call did not write (a workspace shared by overlapping calls) poisons the row
+                    // instead of being summed silently
+                    const float ref = ml4[0], sum = ml4[1], tag = ml4[2];
+                    pm[e][k] = __builtin_bit_cast(uint32_t, tag) == (uint32_t)a.call_id ? ref : __builtin_nanf("");
+                    pl[e][k] = sum;
+                    po[e][k] = *reinterpret_cast<const f32x4*>(a.part_o + row * kD + d0);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < kE; ++e) {
+                float m_new = m_star[e];
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k)
+                    if (bb0 + k <= b_last) m_new = fmaxf(m_new, pm[e][k]);
+                const float mu = m_new == -INFINITY ? 0.0f : m_new;
+                const float keep = fast_exp2(m_star[e] - mu);  // 0 while nothing has been accumulated
+                l[e] *= keep;
+                o[e] *= keep;
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const float wgt = bb0 + k <= b_last ? fast_exp2(pm[e][k] - mu) : 0.0f;
+                    l[e] += pl[e][k] * wgt;
+                    o[e] += po[e][k] * wgt;
+                }
+                m_star[e] = m_new;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kE; ++e) {
+            const int idx = e_base + threadIdx.x + e * kThreads;
+            if (idx >= n_elem) break;
             const int m = idx / (kD / 4), d0 = (idx % (kD / 4)) * 4;
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const int bb = min(bb0 + k, b_last);  // past the end: the last piece again, weighted 0 below
-                const size_t row = (size_t)(bb * 2 + (bb == b_first ? 1 : 0)) * a.m_cap + m;
-                // Ordinary loads are enough on this side (and 0.5 us quicker than device-coherent ones): a piece
-                // was stored through to memory and acknowledged before it was counted; a slot is written once and
-                // read once per launch, so neither this compute unit's L1 nor this die's L2 can hold an older copy
-                // of it from this launch, and copies from earlier launches are dropped when a kernel starts (the same
-                // rule that lets any kernel read what an earlier kernel wrote on another die).
-                const f32x4 ml4 = *reinterpret_cast<const f32x4*>(a.part_ml + row * 4);
-                // a slot that this call did not write (a workspace shared by overlapping calls) poisons the row
-                // instead of being summed silently
-                const float ref = ml4[0], sum = ml4[1], tag = ml4[2];
-                pm[e][k] = __builtin_bit_cast(uint32_t, tag) == (uint32_t)a.call_id ? ref : __builtin_nanf("");
-                pl[e][k] = sum;
-                po[e][k] = *reinterpret_cast<const f32x4*>(a.part_o + row * kD + d0);
+            const f32x4 r = o[e] * (1.0f / l[e]);
+            const int j = m / a.G, h = g * a.G + m % a.G;
+            const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
+            if (a.out_bf16) {
+                ushort4 pk;
+                pk.x = f32_to_bf16_rne(r[0]);
+                pk.y = f32_to_bf16_rne(r[1]);
+                pk.z = f32_to_bf16_rne(r[2]);
+                pk.w = f32_to_bf16_rne(r[3]);
+                *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(a.out) + o_idx) = pk;
+            } else {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + o_idx) = r;
             }
+            if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (m_star[e] + __log2f(l[e])) * kLn2;
         }
-#pragma unroll
-        for (int e = 0; e < kE; ++e) {
-            float m_new = m_star[e];
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k)
-                if (bb0 + k <= b_last) m_new = fmaxf(m_new, pm[e][k]);
-            const float mu = m_new == -INFINITY ? 0.0f : m_new;
-            const float keep = fast_exp2(m_star[e] - mu);  // 0 while nothing has been accumulated
-            l[e] *= keep;
-            o[e] *= keep;
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const float wgt = bb0 + k <= b_last ? fast_exp2(pm[e][k] - mu) : 0.0f;
-                l[e] += pl[e][k] * wgt;
-                o[e] += po[e][k] * wgt;
-            }
-            m_star[e] = m_new;
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < kE; ++e) {
-        const int idx = threadIdx.x + e * kThreads;
-        if (idx >= n_elem) break;
-        const int m = idx / (kD / 4), d0 = (idx % (kD / 4)) * 4;
-        const f32x4 r = o[e] * (1.0f / l[e]);
-        const int j = m / a.G, h = g * a.G + m % a.G;
-        const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
-        if (a.out_bf16) {
-            ushort4 pk;
-            pk.x = f32_to_bf16_rne(r[0]);
-            pk.y = f32_to_bf16_rne(r[1]);
-            pk.z = f32_to_bf16_rne(r[2]);
-            pk.w = f32_to_bf16_rne(r[3]);
-            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(a.out) + o_idx) = pk;
-        } else {
-            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + o_idx) = r;
-        }
-        if (a.lse && d0 == 0) a.lse[(size_t)(q0 + j) * a.H_q + h] = (m_star[e] + __log2f(l[e])) * kLn2;
     }
 }
 
@@ -1080,17 +1133,18 @@ __device__ __forceinline__ void finish_piece(const FastArgs& a, const Segment& s
 // waits for another).
 //
 // attn_stream_kernel builds the schedule itself, from the lengths, at the start of every launch.
-template <int MTMAX, bool TM, bool KV8>
+template <int MTMAX, bool TM, bool KV8, bool WIDE>
 __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
-    long long* pref = reinterpret_cast<long long*>(smem + pref_off());
-    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(smem + scan_off(a.B)),
-                                       reinterpret_cast<int*>(smem + cu_off(a.B)), reinterpret_cast<int*>(smem + ctx_off(a.B)));
+    char* tables = smem + stream_fixed_smem(WIDE);
+    long long* pref = reinterpret_cast<long long*>(tables);
+    const int cmax = build_cost_prefix(a, MTMAX, pref, reinterpret_cast<long long*>(tables + scan_off(a.B)),
+                                       reinterpret_cast<int*>(tables + cu_off(a.B)), reinterpret_cast<int*>(tables + ctx_off(a.B)));
     ShareWalker<true> wk;
     wk.pref = pref;
-    wk.lds_cu = reinterpret_cast<const int*>(smem + cu_off(a.B));
-    wk.lds_ctx = reinterpret_cast<const int*>(smem + ctx_off(a.B));
+    wk.lds_cu = reinterpret_cast<const int*>(tables + cu_off(a.B));
+    wk.lds_ctx = reinterpret_cast<const int*>(tables + ctx_off(a.B));
     // every share is at least as wide as the dearest tile: a workgroup whose share lies inside an
     // item then owns at least one of its tiles
     const long long total = pref[a.B] * a.H_kv;
@@ -1104,8 +1158,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(FastArgs a) {
 
     Segment cur;
     while (wk.next(a, cur)) {
-        const KVStream st = make_stream<TM, KV8>(a, cur);
-        attend_dispatch<MTMAX, TM, KV8, kStreamRT>(a, cur, st, smem);
+        attend_dispatch<MTMAX, TM, KV8, kStreamRT, WIDE>(a, cur, smem, false, 0);
         if (cur.cut) finish_piece<MTMAX>(a, cur, &s_last);
     }
 }
@@ -1148,9 +1201,9 @@ __device__ __forceinline__ void write_record(int32_t* rec, const FastArgs& a, co
 // One workgroup; thread t walks shares t, t + 256, ... twice (count, then write).
 __global__ __launch_bounds__(kThreads) void attn_plan_kernel(FastArgs a, int mt_max, int32_t* plan, int more_cap) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    long long* pref = reinterpret_cast<long long*>(smem + pref_off());
+    long long* pref = reinterpret_cast<long long*>(smem);
     long long* scratch = reinterpret_cast<long long*>(smem + scan_off(a.B));
-    int* cnt = reinterpret_cast<int*>(smem + sched_smem(a.B));  // [kMaxShares] segments of a share, then where its further ones start
+    int* cnt = reinterpret_cast<int*>(smem + tables_bytes(a.B));  // [kMaxShares] segments of a share, then where its further ones start
     const int cmax = build_cost_prefix(a, mt_max, pref, scratch, reinterpret_cast<int*>(smem + cu_off(a.B)),
                                        reinterpret_cast<int*>(smem + ctx_off(a.B)));
     ShareWalker<false> wk;
@@ -1220,7 +1273,7 @@ __global__ __launch_bounds__(kThreads) void attn_plan_kernel(FastArgs a, int mt_
     }
 }
 
-template <int MTMAX, bool TM, bool KV8>
+template <int MTMAX, bool TM, bool KV8, bool WIDE>
 __global__ __launch_bounds__(kThreads) void attn_planned_kernel(FastArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ int s_last;
@@ -1255,10 +1308,7 @@ __global__ __launch_bounds__(kThreads) void attn_planned_kernel(FastArgs a) {
         const int flags = f[9];
         cur.final_out = (flags & 1) != 0; cur.cut = (flags & 2) != 0;
         cur.b_first = f[10]; cur.b_last = f[11]; cur.slot = f[12];
-        KVStream st = make_stream<TM, KV8>(a, cur);
-        st.rec_pages = true;
-        st.pgv = pgv;
-        attend_dispatch<MTMAX, TM, KV8, MTMAX>(a, cur, st, smem);
+        attend_dispatch<MTMAX, TM, KV8, MTMAX, WIDE>(a, cur, smem, true, pgv);
         if (cur.cut) finish_piece<MTMAX>(a, cur, &s_last);
     }
 }
@@ -1355,7 +1405,9 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(GenericArgs a) {
 // How a call is run.
 struct Setup {
     bool fast;   // the stream kernel (bf16, D = 128, P = 16, G <= 16, B <= kMaxB); else one wave per (row, head)
-    int mt_max;  // 16-row query tiles per row group (template argument of the kernel)
+    int mt_max;  // 16-row query tiles a team of waves takes (template argument of the kernel)
+    bool wide;   // row groups of two teams (requests with more than kMaxMT query tiles of rows per KV head)
+    int m_cap;   // rows a partial slot holds
     int nb;      // workgroups of the persistent grid
     int shares_cap;  // shares the workspace is laid out for
     size_t bytes_o, bytes_ml, bytes_cnt;
@@ -1413,12 +1465,14 @@ Setup make_setup(const fsr_attn_params& p, int shares_cap = kMaxShares) {
     // accumulators and both K/V tiles in registers without spilling.
     const long long m_rows = p.max_q_len > 0 ? (long long)G * p.max_q_len : 1 << 20;
     const long long mt = (m_rows + 15) / 16;
-    su.mt_max = mt <= kMaxMT ? (int)mt : 3;
+    su.wide = mt > kMaxMT;
+    su.mt_max = su.wide ? kWideMT : (int)mt;
+    su.m_cap = 16 * su.mt_max * (su.wide ? 2 : 1);
     su.shares_cap = shares_cap;
     su.nb = std::min(persistent_blocks(), shares_cap);
     if (p.max_workgroups > 0) su.nb = std::min(su.nb, p.max_workgroups);
-    su.bytes_o = align_up((size_t)shares_cap * 2 * 16 * su.mt_max * kD * sizeof(float), 256);
-    su.bytes_ml = align_up((size_t)shares_cap * 2 * 16 * su.mt_max * 4 * sizeof(float), 256);
+    su.bytes_o = align_up((size_t)shares_cap * 2 * su.m_cap * kD * sizeof(float), 256);
+    su.bytes_ml = align_up((size_t)shares_cap * 2 * su.m_cap * 4 * sizeof(float), 256);
     su.bytes_cnt = align_up((size_t)(shares_cap + 1) * sizeof(unsigned long long), 256);
     return su;
 }
@@ -1430,7 +1484,7 @@ int cost_base_for(const fsr_attn_params& p, const Setup& su) {
 // What a plan depends on besides the device arrays it was built from.
 uint32_t plan_key_of(const fsr_attn_params& p, const Setup& su) {
     uint32_t h = 2166136261u;
-    const int v[] = {p.B, p.N_cap, p.H_q, p.H_kv, p.max_pages, p.n_pages, su.mt_max, su.nb, cost_base_for(p, su), kSegTiles};
+    const int v[] = {p.B, p.N_cap, p.H_q, p.H_kv, p.max_pages, p.n_pages, su.mt_max, su.wide ? 1 : 0, su.nb, cost_base_for(p, su), kSegTiles};
     for (int x : v) {
         h = (h ^ (uint32_t)x) * 16777619u;
         h ^= h >> 15;
@@ -1442,7 +1496,7 @@ uint32_t plan_key_of(const fsr_attn_params& p, const Setup& su) {
 // segment per share it touches, i.e. at most (items + shares) segments in all.
 size_t plan_more_cap(const fsr_attn_params& p, const Setup& su) {
     const int G = p.H_q / p.H_kv;
-    const long long per_group = std::max(16 * su.mt_max / G, 1);
+    const long long per_group = std::max(16 * su.mt_max / G, 1) * (su.wide ? 2 : 1);
     const long long items = (long long)p.H_kv * ((long long)p.B + p.N_cap / per_group + 1);
     return (size_t)(items + kMaxShares);
 }
@@ -1490,7 +1544,7 @@ void fill_common(FastArgs& a, const fsr_attn_params* p, const Setup& su, const i
     a.bt = block_tables; a.ctx = ctx_lens; a.cu_q = cu_q;
     a.B = p->B; a.H_q = p->H_q; a.H_kv = p->H_kv; a.G = p->H_q / p->H_kv;
     a.max_pages = p->max_pages; a.n_pages = p->n_pages;
-    a.nb = su.nb; a.m_cap = 16 * su.mt_max;
+    a.nb = su.nb; a.m_cap = su.m_cap; a.wide = su.wide ? 1 : 0;
     a.seg_tiles = kSegTiles;
     a.cost_base = cost_base_for(*p, su);
     a.plan = nullptr; a.plan_key = 0;
@@ -1545,24 +1599,28 @@ int attention_call(const void* q, const void* k_cache, const void* v_cache, cons
             a.plan_key = key;
         }
         const dim3 grid(su.nb), block(kThreads);
-        const size_t smem = plan ? planned_smem(su.mt_max) : sched_smem(p->B);
-#define FSR_LAUNCH_K(KERNEL, MT)                                                             \
+        const size_t smem = plan ? planned_smem(su.mt_max, su.wide) : stream_fixed_smem(su.wide) + tables_bytes(p->B);
+#define FSR_LAUNCH_K(KERNEL, MT, WIDE)                                                       \
     if (kv8 && p->kv_layout == FSR_KV_TOKEN_MAJOR)                                           \
-        hipLaunchKernelGGL((KERNEL<MT, true, true>), grid, block, smem, s, a);               \
+        hipLaunchKernelGGL((KERNEL<MT, true, true, WIDE>), grid, block, smem, s, a);         \
     else if (kv8)                                                                            \
-        hipLaunchKernelGGL((KERNEL<MT, false, true>), grid, block, smem, s, a);              \
+        hipLaunchKernelGGL((KERNEL<MT, false, true, WIDE>), grid, block, smem, s, a);        \
     else if (p->kv_layout == FSR_KV_TOKEN_MAJOR)                                             \
-        hipLaunchKernelGGL((KERNEL<MT, true, false>), grid, block, smem, s, a);              \
+        hipLaunchKernelGGL((KERNEL<MT, true, false, WIDE>), grid, block, smem, s, a);        \
     else                                                                                     \
-        hipLaunchKernelGGL((KERNEL<MT, false, false>), grid, block, smem, s, a)
-#define FSR_LAUNCH(MT)                                    \
-    if (plan) { FSR_LAUNCH_K(attn_planned_kernel, MT); }  \
-    else { FSR_LAUNCH_K(attn_stream_kernel, MT); }
-        switch (su.mt_max) {
-            case 1: FSR_LAUNCH(1); break;
-            case 2: FSR_LAUNCH(2); break;
-            case 3: FSR_LAUNCH(3); break;
-            default: FSR_LAUNCH(4); break;
+        hipLaunchKernelGGL((KERNEL<MT, false, false, WIDE>), grid, block, smem, s, a)
+#define FSR_LAUNCH(MT, WIDE)                                    \
+    if (plan) { FSR_LAUNCH_K(attn_planned_kernel, MT, WIDE); }  \
+    else { FSR_LAUNCH_K(attn_stream_kernel, MT, WIDE); }
+        if (su.wide) {
+            FSR_LAUNCH(kWideMT, true);
+        } else {
+            switch (su.mt_max) {
+                case 1: FSR_LAUNCH(1, false); break;
+                case 2: FSR_LAUNCH(2, false); break;
+                case 3: FSR_LAUNCH(3, false); break;
+                default: FSR_LAUNCH(4, false); break;
+            }
         }
 #undef FSR_LAUNCH
 #undef FSR_LAUNCH_K
@@ -1620,7 +1678,7 @@ extern "C" int fsr_attn_plan(const int32_t* block_tables, const int32_t* ctx_len
     FastArgs a{};
     fill_common(a, p, su, block_tables, ctx_lens, cu_q);
     a.plan_key = plan_key_of(*p, su);
-    const size_t smem = sched_smem(p->B) + (size_t)kMaxShares * sizeof(int);
+    const size_t smem = tables_bytes(p->B) + (size_t)kMaxShares * sizeof(int);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kThreads), smem, (hipStream_t)stream, a, su.mt_max, (int32_t*)plan,
                        (int)plan_more_cap(*p, su));
     rc = check_launch("attn_plan_kernel");
@@ -1650,7 +1708,7 @@ extern "C" int fsr_verify_attention_planned(const void* q, const void* k_cache, 
 namespace {
 constexpr int kStaticShares = 256;
 constexpr size_t kStaticScratchBytes =
-    (size_t)kStaticShares * 2 * 16 * kMaxMT * (kD + 4) * sizeof(float) + (size_t)(kStaticShares + 1) * sizeof(unsigned long long) + 3 * 256;
+    (size_t)kStaticShares * 2 * 16 * 2 * kWideMT * (kD + 4) * sizeof(float) + (size_t)(kStaticShares + 1) * sizeof(unsigned long long) + 3 * 256;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kMaxDevices = 64;

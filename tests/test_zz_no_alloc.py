@@ -20,7 +20,7 @@ def _ptr(t):
 def test_static_scratch_entry_point_matches_workspace_entry_point(oracle):
     from paper_2604_20503_amd import binding as B
     lib = B.load_library()
-    assert 16 << 20 < lib.fsr_static_scratch_bytes() < 20 << 20
+    assert 16 << 20 < lib.fsr_static_scratch_bytes() < 32 << 20
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     cases = [dict(rep=41, ctx_lens=[1500, 45, 513, 128, 3000, 77, 2047, 900, 1, 0, 4000, 333], spec_lens=[8, 3, 6, 0, 2, 5, 8, 1, 4, 2, 7, 8]),
              dict(rep=42, ctx_lens=[700, 31, 260], spec_lens=[2, 0, 5])]          # second call: smaller input
