@@ -30,6 +30,7 @@
 #include <atomic>
 #include <map>
 #include <mutex>
+#include <type_traits>
 
 #include "common.hpp"
 #include "device_utils.hpp"
@@ -683,14 +684,15 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     };
 
     // raw scores of all query tiles with the keys a row may not see set to -inf
-    auto masked_scores = [&](int kb, const f32x4 (&s)[MT][2], float (&x)[MT][8]) {
+    // (may_mask = false: the caller knows that every row sees every key of the tile)
+    auto masked_scores = [&](int kb, const f32x4 (&s)[MT][2], float (&x)[MT][8], bool may_mask = true) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) x[mt][kt * 4 + e] = s[mt][kt][e];
-        if (kb + kTile > c + j0 + 1) {  // only the item's last keys are causal-masked or past the end
+        if (may_mask && kb + kTile > c + j0 + 1) {  // only the item's last keys are causal-masked or past the end
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -758,11 +760,11 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     // its fair share of HBM bandwidth and not by load latency plus its own arithmetic.
     constexpr float kFastSlack = 64.0f;
     bool lane_ok = true;
-    auto fast_softmax_pv = [&](int kb, const f32x4 (&s)[MT][2]) {
+    auto fast_softmax_pv = [&](int kb, const f32x4 (&s)[MT][2], bool may_mask) {
         bf16x8 vop[8];
         load_vops(vop);
         float x[MT][8], lane_max[MT];
-        masked_scores(kb, s, x);
+        masked_scores(kb, s, x, may_mask);
         bool any = false;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -792,18 +794,29 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         // after the tile's arithmetic, not before it: HBM is saturated either way, and the fewer bytes the
         // chip keeps queued the sooner a segment's first tiles, its partials and its arrival count come back
         // (measured: 0.2 to 0.7 % per launch on every workload shape).
-        auto fast_tile = [&](Tile& tl, int t) {
+        auto fast_tile = [&](Tile& tl, int t, auto plain) {
             const bool real = t < nw;
             if (real) stage_and_scores(tl, kb0 + t * step, s);
             __builtin_amdgcn_sched_barrier(0);
-            if (real) fast_softmax_pv(kb0 + t * step, s);
+            if (real) fast_softmax_pv(kb0 + t * step, s, !decltype(plain)::value);
             __builtin_amdgcn_sched_barrier(0);
             issue(tl, t + kDepth);
             __builtin_amdgcn_sched_barrier(0);
         };
-        for (int t = 0; t < nw; t += kDepth) {
-            fast_tile(ta, t);
-            fast_tile(tb, t + 1);
+        // The wave's first n_plain tiles lie wholly below the first row's causal limit (every row sees every
+        // key): pairs of them run a loop with no masking code in it -- as a select per score inside the one loop
+        // it cost a third of the loop's vector instructions, most of them copies between the two register
+        // files -- and the rest, the item's last few tiles, the general loop.
+        const int below = c + j0 + 1 - kTile - kb0;  // tile t is plain iff t * step <= below
+        const int n_plain = below < 0 ? 0 : min(below / step + 1, nw);
+        int t = 0;
+        for (; t + 1 < n_plain; t += kDepth) {
+            fast_tile(ta, t, std::true_type{});
+            fast_tile(tb, t + 1, std::true_type{});
+        }
+        for (; t < nw; t += kDepth) {
+            fast_tile(ta, t, std::false_type{});
+            fast_tile(tb, t + 1, std::false_type{});
         }
         redo = __builtin_amdgcn_ballot_w64(!lane_ok) != 0;
     }
