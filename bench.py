@@ -351,6 +351,29 @@ def measured_traffic(kernel, workload):
     return None, None
 
 
+
+def plain_read_rates(fsr, torch, gib=2, reps=5):
+    """GB/s of fsr_hbm_read_probe (plain streaming loads over a buffer larger than the on-die caches), front
+    to back and in scattered 4 KB blocks (how a paged cache with 16-token pages lays out one head's K or V),
+    timed with HIP events on the launch stream: the practical ceilings next to which `achieved` is read."""
+    src = torch.zeros(gib << 30, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    out = {}
+    with torch.cuda.stream(stream):
+        sink = fsr.hbm_read_probe(src)
+        for name, scatter in (("plain_read_GBs", False), ("scattered_4k_read_GBs", True)):
+            fsr.hbm_read_probe(src, sink, scatter_4k=scatter)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, e in ev:
+                a.record(stream)
+                fsr.hbm_read_probe(src, sink, scatter_4k=scatter)
+                e.record(stream)
+            torch.cuda.synchronize()
+            out[name] = (gib << 30) / (statistics.mean(a.elapsed_time(e) for a, e in ev) * 1e-3) / 1e9
+    del src
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -423,7 +446,7 @@ def main():
             "roofline": {"bound": "hbm", "kernel": f"{attn_kernel} (verify_attention, one launch per layer and chunk; all chunks)",
                          "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                          "traffic": None, "algorithmic_bytes_per_launch": attn_bytes / len(table),
-                         "launch_us": attn_us / len(table)},
+                         "launch_us": attn_us / len(table), **plain_read_rates(fsr, torch)},
         }
         if not args.no_cpu_baseline:
             base, ref = cpu_baseline(b, args.layers)
@@ -503,7 +526,7 @@ def main():
                                                + ("" if args.no_plan else "; the step's one attn_plan_kernel launch is inside the figure") + ")",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_src, "algorithmic_bytes_per_launch": attn_bytes,
-                     "launch_us": attn_ms * 1e3},
+                     "launch_us": attn_ms * 1e3, **plain_read_rates(fsr, torch)},
         "kernels": kernel_figures(b, st, call_us),
     }
     if args.overlap > 0:

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     frontier_commit,
     frontier_init,
     frontier_plan,
+    hbm_read_probe,
     kv_append,
     kv_append_kv8,
     last_error,
@@ -35,6 +36,6 @@ from .frontier import verify_chunked  # noqa: F401
 
 __all__ = [
     "FsrError", "accept_workspace_bytes", "attn_path", "attn_plan", "attn_workspace_bytes", "frontier_commit", "frontier_init",
-    "frontier_plan", "kv_append", "kv_append_kv8", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
+    "frontier_plan", "hbm_read_probe", "kv_append", "kv_append_kv8", "last_error", "library_path", "load_library", "prune_compact", "prune_restore", "prune_scatter",
     "spec_accept", "survivor_compact", "survivor_mask", "topk_rank_check", "verify_attention", "verify_attention_kv8", "verify_attention_static", "verify_chunked", "version",
 ]

@@ -25,6 +25,7 @@ SYMBOLS = [
     "fsr_verify_attention_planned", "fsr_verify_attention_static", "fsr_static_scratch_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_survivor_compact", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
+    "fsr_hbm_read_probe",
 ]
 
 
@@ -475,3 +476,15 @@ def frontier_commit(spec_lens, chunk_len, accepted_len, n_emitted, emitted, pos,
         _ptr(n_emitted, torch.int32), _ptr(emitted, torch.int32), ctypes.c_int32(emitted.shape[1]),
         _ptr(pos, torch.int32), _ptr(active, torch.int32), _ptr(n_out, torch.int32), _ptr(acc_total, torch.int32),
         _ptr(out_tokens, torch.int32), ctypes.c_int32(B), ctypes.c_int32(out_tokens.shape[1]), _stream()))
+
+
+def hbm_read_probe(src: torch.Tensor, sink: Optional[torch.Tensor] = None, workgroups: int = 4096, scatter_4k: bool = False):
+    """fsr_hbm_read_probe: one launch that streams all of ``src`` (device bytes, a multiple of 32768) with
+    plain loads, front to back or (scatter_4k) in scattered 4 KB blocks; returns the sink tensor (int64
+    [workgroups]).  Measurement aid for bench.py."""
+    lib = load_library()
+    if sink is None:
+        sink = torch.empty(workgroups, dtype=torch.int64, device=src.device)
+    _check(lib.fsr_hbm_read_probe(_ptr(src, name="src"), ctypes.c_size_t(src.numel() * src.element_size()),
+                                  _ptr(sink, torch.int64, name="sink"), ctypes.c_int32(workgroups), ctypes.c_int32(int(scatter_4k)), _stream()))
+    return sink

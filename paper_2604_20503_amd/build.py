@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfaser_verify.so")
-SOURCES = ["controller.hip", "greedy_accept.hip", "kv_append.hip", "library.hip", "prune_compact.hip", "rank_check.hip", "spec_accept.hip", "verify_attention.hip"]
+SOURCES = ["controller.hip", "greedy_accept.hip", "hbm_probe.hip", "kv_append.hip", "library.hip", "prune_compact.hip", "rank_check.hip", "spec_accept.hip", "verify_attention.hip"]
 # packed fp32 ops are switched off on purpose (the compiler would otherwise form v_pk_*_f32)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -151,3 +151,25 @@ def test_plan_reused_across_layers_in_a_graph_and_refused_for_other_shapes(fsr, 
                          max_q_len=mq, plan=plan)
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(max_workgroups=3), dict(max_workgroups=37), dict(kv_layout=1)])
+@pytest.mark.parametrize("heads", [(32, 8), (64, 8), (48, 16), (16, 1)])
+def test_wide_row_groups_take_two_teams_of_waves(fsr, oracle, heads, kw):
+    """Suffixes whose G * q_len rows exceed four query tiles: row groups of two teams (some with a short or
+    empty second team, some requests with several groups), cut by share boundaries at small grids; the planned and
+    the self-scheduling kernel agree bit for bit and with the oracle."""
+    H_q, H_kv = heads
+    announce(f"wide row groups heads={heads} {kw}")
+    ctx = [700, 0, 1, 31, 33, 257, 1500, 2047, 90, 3100, 16, 640]
+    spec = [32, 24, 12, 13, 6, 25, 11, 30, 0, 23, 17, 5]
+    b = workloads.make_batch(2, rep=90 + H_q, with_probs=False, H_q=H_q, H_kv=H_kv, ctx_lens=ctx, spec_lens=spec)
+    d = DeviceBatch(b, probs=False)
+    if kw.get("kv_layout"):
+        d.k_cache = d.k_cache.transpose(1, 2).contiguous()
+        d.v_cache = d.v_cache.transpose(1, 2).contiguous()
+    o_ref, lse_ref = ref_of(oracle, b)
+    (o0, l0), (o1, l1) = both_ways(fsr, b, d, torch.float32, b.S_max + 1, **kw)
+    assert same_bits(o0, o1) and same_bits(l0, l1)
+    check_attention(o1, o_ref, "bf16", b.N)
+    np.testing.assert_allclose(l1.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
