@@ -352,6 +352,27 @@ def measured_traffic(kernel, workload):
 
 
 
+def probe_table(fsr, torch, gib=2, reps=5):
+    """--probe: GB/s of the plain-read probe in its three access patterns against the workgroup count (256
+    workgroups = one per compute unit, 8 MB in flight; the attention kernel keeps up to 33 MB in flight)."""
+    src = torch.zeros(gib << 30, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    table = {}
+    with torch.cuda.stream(stream):
+        for name, mode in (("front_to_back", 0), ("scattered_4k_blocks", 1), ("scattered_4k_blocks_as_64_byte_row_segments", 2)):
+            for wg in (128, 256, 1024, 4096):
+                sink = torch.empty(wg, dtype=torch.int64, device="cuda")
+                fsr.hbm_read_probe(src, sink, wg, mode)
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+                for a, e in ev:
+                    a.record(stream)
+                    fsr.hbm_read_probe(src, sink, wg, mode)
+                    e.record(stream)
+                torch.cuda.synchronize()
+                table.setdefault(name, {})[str(wg)] = round((gib << 30) / (statistics.mean(a.elapsed_time(e) for a, e in ev) * 1e-3) / 1e9, 1)
+    return {"probe": "fsr_hbm_read_probe", "bytes": gib << 30, "unit": "GB/s", "by_workgroups": table}
+
+
 def plain_read_rates(fsr, torch, gib=2, reps=5):
     """GB/s of fsr_hbm_read_probe (plain streaming loads over a buffer larger than the on-die caches), front
     to back and in scattered 4 KB blocks (how a paged cache with 16-token pages lays out one head's K or V),
@@ -395,6 +416,7 @@ def main():
     ap.add_argument("--overlap", type=int, default=0, metavar="N",
                     help="also measure the step's attention on a stream that owns all but N compute units next to a "
                          "stand-in drafter on a stream that owns those N (adds an \"overlap\" object to the JSON line)")
+    ap.add_argument("--probe", action="store_true", help="time only the plain-read probe (three access patterns) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that hardware byte counters of a "
                          "profiled run can be scaled")
@@ -417,6 +439,10 @@ def main():
     b = workloads.make_batch(args.workload)
     drafts = int(b.spec_lens.sum())
     attn_kernel = "attn_stream_kernel" if args.no_plan else "attn_planned_kernel"
+
+    if args.probe:
+        print(json.dumps(probe_table(fsr, torch)))
+        return
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")

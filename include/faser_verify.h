@@ -428,14 +428,16 @@ int fsr_frontier_commit(const int32_t* spec_lens, const int32_t* chunk_len,
  * src (device, 16-byte aligned; bytes a positive multiple of 32768) with plain 16-byte loads, eight
  * in flight per thread, `workgroups` workgroups of 256 threads striding over the buffer, and
  * writes the XOR of what each workgroup read to sink[workgroup] (device, `workgroups` words;
- * overwritten).  scatter_4k != 0: the buffer's 4 KB blocks are visited in a scattered order (a
- * fixed permutation; bytes must then be a power of two) instead of front to back -- the
- * granularity at which a paged cache with 16-token pages stores one head's K or V bytes.
+ * overwritten).  scatter_4k = 0: front to back.  1: the buffer's 4 KB blocks are visited in a
+ * scattered order (a fixed permutation; bytes must then be a power of two) -- the granularity at
+ * which a paged cache with 16-token pages stores one head's K or V bytes.  2: scattered blocks
+ * again, each read as 16 rows of 256 bytes with a load taking 64 bytes of every row (K fetched
+ * straight into a matrix-operand layout) instead of 1 KB of consecutive bytes.
  * bench.py times it beside the attention kernel: the rate this device delivers
  * to trivially parallel streaming reads is the practical ceiling the kernel's achieved HBM rate
  * is to be read against (the roofline fraction itself stays against the published 8 TB/s).
  * Errors: FSR_EINVAL for null or misaligned pointers, a size that is not such a multiple (or
- * not a power of two with scatter_4k), or workgroups outside 1..65535.
+ * not a power of two with scatter_4k != 0), or workgroups outside 1..65535.
  */
 int fsr_hbm_read_probe(const void* src, size_t bytes, unsigned long long* sink, int32_t workgroups,
                        int32_t scatter_4k, void* stream);

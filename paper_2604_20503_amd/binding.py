@@ -478,10 +478,10 @@ def frontier_commit(spec_lens, chunk_len, accepted_len, n_emitted, emitted, pos,
         _ptr(out_tokens, torch.int32), ctypes.c_int32(B), ctypes.c_int32(out_tokens.shape[1]), _stream()))
 
 
-def hbm_read_probe(src: torch.Tensor, sink: Optional[torch.Tensor] = None, workgroups: int = 4096, scatter_4k: bool = False):
+def hbm_read_probe(src: torch.Tensor, sink: Optional[torch.Tensor] = None, workgroups: int = 4096, scatter_4k: int = 0):
     """fsr_hbm_read_probe: one launch that streams all of ``src`` (device bytes, a multiple of 32768) with
-    plain loads, front to back or (scatter_4k) in scattered 4 KB blocks; returns the sink tensor (int64
-    [workgroups]).  Measurement aid for bench.py."""
+    plain loads: front to back (0), in scattered 4 KB blocks (1), or those blocks as 64-byte segments of 16
+    rows per load (2); returns the sink tensor (int64 [workgroups]).  Measurement aid for bench.py."""
     lib = load_library()
     if sink is None:
         sink = torch.empty(workgroups, dtype=torch.int64, device=src.device)
