@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void greedy_argmax_kernel(const float* __
     const int body0 = v0 + head, n_vec = (v1 - body0) / 4;
     const u32x4* vec = reinterpret_cast<const u32x4*>(z + body0);
     for (int k = threadIdx.x; k < n_vec; k += kThreads) {
-        const u32x4 w = vec[k];
+        const u32x4 w = __builtin_nontemporal_load(vec + k);  // a row is streamed once
         const uint32_t w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
         const int v = body0 + 4 * k;
         unsigned long long c = make_key(w0, v);

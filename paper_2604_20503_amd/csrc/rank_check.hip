@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void rank_count_kernel(RankArgs a) {
     const int body0 = v0 + head, n_vec = (v1 - body0) / kPer;
     const u32x4* vec = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(a.logits) + base + body0);
     for (int k = threadIdx.x; k < n_vec; k += kThreads) {
-        const u32x4 w = vec[k];
+        const u32x4 w = __builtin_nontemporal_load(vec + k);  // a row is streamed once
         // elements go to scalars first: __builtin_bit_cast applied to a vector-element expression was
         // seen to read element 0 for every index
         const uint32_t w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];

@@ -64,7 +64,7 @@ constexpr int kRedStride = kD + 4;  // padded row of the wave-merge buffer (floa
 // LDS map, fixed part: [V tiles of the 4 waves | wave-merge buffer] (shared region), wave maxima and
 // sums, Q^T operands.  The merge buffer holds the accumulators of RT query tiles of all 4 waves at a
 // time: merging a segment's query tiles in one batch costs two workgroup barriers instead of two per
-// tile (measured: 2.4 us -> 1.1 us for three tiles).
+// tile (what a merge costs is mostly LDS traffic, though: about 0.8 us per query tile either way).
 constexpr int kVTileBytes = kTile * kD * 2;
 constexpr int kRedBytes = kWaves * 16 * kRedStride * 4;
 constexpr int kMlBytes = 2 * kWaves * 16 * kMaxMT * 4;
