@@ -19,6 +19,7 @@ _lib = None
 F32, BF16 = 0, 1
 PROBS, LOGITS, GREEDY = 0, 1, 2
 KV_HEAD_MAJOR, KV_TOKEN_MAJOR = 0, 1
+EWS = -4  # FSR_EWS: workspace missing, too small, or (binding only) still in use on another stream
 
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_attn_path", "fsr_attn_plan_bytes", "fsr_attn_plan",
@@ -170,6 +171,32 @@ def attn_plan(q, k_cache, block_tables, ctx_lens, cu_q, *, scale, out_dtype=None
     return plan
 
 
+# One attention call in flight per workspace (the pieces of items cut by share boundaries go through it):
+# a caller-supplied workspace that was last used on another stream is refused while that stream's call
+# may still be running.  Workspaces used under HIP-graph capture are not tracked (no event can be recorded).
+_ws_last_use = {}
+
+
+def _guard_workspace(workspace):
+    if workspace is None or torch.cuda.is_current_stream_capturing():
+        return None
+    key = workspace.data_ptr()
+    stream = torch.cuda.current_stream()
+    last = _ws_last_use.get(key)
+    if last is not None and last[0] != stream.cuda_stream and not last[1].query():
+        raise FsrError(EWS, "this attention workspace is still in use by a call on another stream: "
+                                     "give every stream (and every graph that may replay concurrently) its own workspace")
+    return key, stream
+
+
+def _note_workspace_use(token):
+    if token is not None:
+        key, stream = token
+        ev = torch.cuda.Event()
+        ev.record(stream)
+        _ws_last_use[key] = (stream.cuda_stream, ev)
+
+
 def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_q, *, scale, out=None, lse=None,
                      out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR, plan=None):
     """fsr_verify_attention.  q [N_cap,H_q,D]; caches [n_pages,H_kv,P,D]; returns (out, lse).
@@ -188,6 +215,7 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
         raise ValueError("cu_q must have B+1 entries and block_tables B rows")
     need = ctypes.c_size_t(0)
     _check(lib.fsr_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(need)))
+    token = _guard_workspace(workspace)
     if workspace is None and need.value:
         workspace = torch.empty(need.value, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -197,6 +225,7 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
             _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
             _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"), _ptr(lse, torch.float32, "lse"), ctypes.byref(p),
             _ptr(plan, name="plan"), _ptr(workspace, name="workspace"), ctypes.c_size_t(ws_bytes), _stream()))
+        _note_workspace_use(token)
         return out, lse
     _check(lib.fsr_verify_attention(
         _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
@@ -204,6 +233,7 @@ def verify_attention(q, k_cache, v_cache, block_tables, ctx_lens, spec_lens, cu_
         _ptr(spec_lens, torch.int32, "spec_lens"), _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"),
         _ptr(lse, torch.float32, "lse"), ctypes.byref(p), _ptr(workspace, name="workspace"),
         ctypes.c_size_t(ws_bytes), _stream()))
+    _note_workspace_use(token)
     return out, lse
 
 

@@ -243,3 +243,32 @@ def test_graph_of_launches_on_one_workspace_with_two_cache_sets(fsr, oracle):
             torch.cuda.synchronize()
             for l in range(8):
                 assert torch.equal(outs[l].view(torch.int16), eager[l].view(torch.int16)), (rep, l)
+
+
+def test_binding_refuses_a_workspace_in_use_on_another_stream(fsr, oracle):
+    """One call in flight per workspace: the binding refuses a workspace whose last call, on another stream, may
+    still be running, and takes it again once that stream has drained."""
+    announce("workspace shared by two streams")
+    b = workloads.make_batch(2, rep=77, with_probs=False, ctx_lens=[300, 45, 513, 700], spec_lens=[3, 0, 8, 5])
+    d = DeviceBatch(b, probs=False)
+    ws = torch.empty(fsr.attn_workspace_bytes(B=b.B, N_cap=b.N, H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, max_pages=b.max_pages,
+                                              n_pages=b.n_pages, dtype=torch.bfloat16, out_dtype=torch.float32, max_q_len=b.S_max + 1),
+                     dtype=torch.uint8, device="cuda")
+    args = (d.q, d.k_cache, d.v_cache, d.block_tables, d.ctx_lens, d.spec_lens, d.cu_q)
+    kw = dict(scale=b.scale, out_dtype=torch.float32, workspace=ws, max_q_len=b.S_max + 1)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s1):
+        torch.cuda._sleep(200_000_000)          # keeps s1 busy for tens of milliseconds
+        o1, _ = fsr.verify_attention(*args, **kw)
+    with torch.cuda.stream(s2):
+        with pytest.raises(fsr.FsrError):
+            fsr.verify_attention(*args, **kw)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s2):
+        o2, _ = fsr.verify_attention(*args, **kw)
+    torch.cuda.synchronize()
+    o_ref, _ = oracle.verify_attention(b.q, b.k_cache, b.v_cache, b.block_tables, b.ctx_lens, b.cu_q, H_q=b.H_q, H_kv=b.H_kv,
+                                       D=b.D, P=b.P, dtype=b.dtype, scale=b.scale)
+    check_attention(o1, o_ref, "bf16", b.N)
+    check_attention(o2, o_ref, "bf16", b.N)
