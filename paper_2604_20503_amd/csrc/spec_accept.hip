@@ -31,6 +31,7 @@ namespace {
 constexpr int kChunk = 4096;        // vocabulary tokens per chunk
 constexpr int kThreads = 256;       // threads per block in stats / partials / select
 constexpr int kPerThread = kChunk / kThreads;  // 16 contiguous tokens per thread in select
+constexpr int kMaxSampleGroup = 8;  // accept_sample: a workgroup takes 1, 2, 4 or 8 consecutive chunks (see launch_all)
 constexpr int kMaxChunksLds = 256;  // chunk masses of a request that the selecting workgroup keeps in LDS (vocabularies up to 2^20)
 
 enum : int { kCaseNone = 0, kCaseResidual = 1, kCaseTarget = 2 };
@@ -332,20 +333,21 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// sample: request i = blockIdx.y; this workgroup owns chunk c = blockIdx.x of the vocabulary.
-// grid = (n_chunks, B)
+// sample: request i = blockIdx.y; this workgroup owns chunks kSampleGroup * blockIdx.x .. + kSampleGroup - 1 of the
+// vocabulary.  grid = (ceil(n_chunks / kSampleGroup), B)
 // ---------------------------------------------------------------------------------------
-template <int MODE, typename RT>
+template <int MODE, typename RT, int kSampleGroup>
 __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const float* __restrict__ u_sample,
     int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int V, int S_max, double T) {
-    __shared__ double smem[kThreads / 64];
+    __shared__ double s_part[kThreads / 64][2 * kSampleGroup];
     __shared__ double s_wave[kThreads / 64];
     __shared__ int s_i[kThreads / 64];
     __shared__ double s_base, s_thr;
     __shared__ int s_chunk, s_fallback, s_last;
     __shared__ double s_mass[2 * kMaxChunksLds];
-    const int c = blockIdx.x, nc = gridDim.x, i = blockIdx.y;
+    const int nc = n_chunks_of(V), i = blockIdx.y;
+    const int c_first = blockIdx.x * kSampleGroup, n_here = min(kSampleGroup, nc - c_first);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
     Decision dec = ws.dec[i];
@@ -355,24 +357,52 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     const RT* trow = p_target + (size_t)dec.t_row * V;
     const RT* drow = p_draft + (size_t)dec.d_row * V;
     const bool vec_t = row_vec_ok(trow), vec_d = row_vec_ok(drow);
+    // A workgroup takes kSampleGroup consecutive chunks: the chain every workgroup goes through (decision record,
+    // row loads, reduction, store-through, arrival count) is paid once per 128 KB instead of once per 32 KB.  Each
+    // chunk's mass is reduced exactly as if it had a workgroup to itself (thread sums, wave sums, waves in order).
     {
-        const int e0 = c * kChunk;
-        double sr = 0.0, st = 0.0;
+        double sr[kSampleGroup], st[kSampleGroup];
 #pragma unroll
-        for (int k = 0; k < kPerThread / 4; ++k) {
-            const int e = e0 + (k * kThreads + threadIdx.x) * 4;
-            double res[4], tgt[4];
-            quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
-            sr += (res[0] + res[1]) + (res[2] + res[3]);
-            st += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+        for (int cc = 0; cc < kSampleGroup; ++cc) {
+            sr[cc] = st[cc] = 0.0;
+            if (cc < n_here) {
+                const int e0 = (c_first + cc) * kChunk;
+#pragma unroll
+                for (int k = 0; k < kPerThread / 4; ++k) {
+                    const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+                    double res[4], tgt[4];
+                    quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
+                    sr[cc] += (res[0] + res[1]) + (res[2] + res[3]);
+                    st[cc] += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+                }
+            }
         }
-        sr = block_sum(sr, smem);
-        st = block_sum(st, smem);
+#pragma unroll
+        for (int cc = 0; cc < kSampleGroup; ++cc) {
+            sr[cc] = wave_sum(sr[cc]);
+            st[cc] = wave_sum(st[cc]);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int cc = 0; cc < kSampleGroup; ++cc) {
+                s_part[w][2 * cc] = sr[cc];
+                s_part[w][2 * cc + 1] = st[cc];
+            }
+        }
+        __syncthreads();
         if (threadIdx.x == 0) {
-            publish_f64(ws.mass_res + (size_t)i * nc + c, sr);
-            publish_f64(ws.mass_tgt + (size_t)i * nc + c, st);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // both are in memory before the arrival is counted
-            s_last = atomicAdd(ws.arrivals + i, 1u) == (unsigned)nc - 1u;
+            for (int cc = 0; cc < n_here; ++cc) {
+                double tr = 0.0, tt = 0.0;
+#pragma unroll
+                for (int k = 0; k < kThreads / 64; ++k) {
+                    tr += s_part[k][2 * cc];
+                    tt += s_part[k][2 * cc + 1];
+                }
+                publish_f64(ws.mass_res + (size_t)i * nc + c_first + cc, tr);
+                publish_f64(ws.mass_tgt + (size_t)i * nc + c_first + cc, tt);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // all are in memory before the arrivals are counted
+            s_last = atomicAdd(ws.arrivals + i, (unsigned)n_here) + (unsigned)n_here == (unsigned)nc;
         }
         __syncthreads();
         if (!s_last) return;
@@ -498,8 +528,18 @@ int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_token
     hipLaunchKernelGGL((accept_decide_kernel<MODE, RT>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
                        cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T);
     if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
-    hipLaunchKernelGGL((accept_sample_kernel<MODE, RT>), dim3(nc, p.B), dim3(kThreads), 0, s, p_target, p_draft, u_sample, n_emitted,
-                       emitted, ws, p.V, p.S_max, T);
+    // chunks per workgroup: as many as leave the device about four workgroups per compute unit (a small batch
+    // keeps one chunk per workgroup: there the call is a latency chain and parallelism is what shortens it)
+    int group = kMaxSampleGroup;
+    while (group > 1 && (long long)p.B * ((nc + group - 1) / group) < 1024) group >>= 1;
+#define FSR_SAMPLE(G)                                                                                                          \
+    hipLaunchKernelGGL((accept_sample_kernel<MODE, RT, G>), dim3((nc + G - 1) / G, p.B), dim3(kThreads), 0, s, p_target, p_draft, \
+                       u_sample, n_emitted, emitted, ws, p.V, p.S_max, T)
+    if (group == 8) FSR_SAMPLE(8);
+    else if (group == 4) FSR_SAMPLE(4);
+    else if (group == 2) FSR_SAMPLE(2);
+    else FSR_SAMPLE(1);
+#undef FSR_SAMPLE
     return check_launch("accept_sample_kernel");
 }
 
