@@ -73,7 +73,9 @@ constexpr int kWideMT = 3;  // query tiles per team of a two-team segment (see a
 constexpr int kQTeamBytes = kWideMT * 4 * 64 * 16;
 template <int RT, bool WIDE>
 struct Lds {
-    static constexpr int kStage = kWaves * 2 * kVTileBytes > RT * kRedBytes ? kWaves * 2 * kVTileBytes : RT * kRedBytes;  // (K tile, V tile) per wave
+    // a wave's own region: its K and V tiles while it streams, its accumulators (RT query tiles) when it merges
+    static constexpr int kWaveRegion = 2 * kVTileBytes > RT * (kRedBytes / kWaves) ? 2 * kVTileBytes : RT * (kRedBytes / kWaves);
+    static constexpr int kStage = kWaves * kWaveRegion;
     static constexpr int kMl = kStage;
     static constexpr int kQ = kMl + kMlBytes;  // Q^T operands of the current item: [query tile * 4][64 lanes][16 B], per team
     static constexpr int kFixed = kQ + (WIDE ? 2 * kQTeamBytes : kQBytes);
@@ -556,7 +558,7 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
     const int G = a.G;
     const int M_g = G * rows_g;
     const int kv_total = uniform(st.kv_total), kb0 = uniform(st.kb0), nw = uniform(st.nw), step = uniform(st.step);
-    char* kbuf = smem + w * 2 * kVTileBytes;  // the wave's K tile (where K goes through LDS), then its V tile
+    char* kbuf = smem + w * L::kWaveRegion;  // the wave's K tile (where K goes through LDS), then its V tile
     char* vbuf = kbuf + kVTileBytes;
 
     const int vw_even = vtile_off(lg, li), vw_odd = vtile_off(4 + lg, li) - 4 * 256;  // LDS store offsets (+ 1024 r)
@@ -940,12 +942,16 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
         l_run[mt] += __shfl_xor(l_run[mt], 32, 64);
     }
 
-    // ---- merge the waves of each team (each saw a disjoint set of keys)
+    // ---- merge the waves of each team (each saw a disjoint set of keys).  A wave puts its exponent references,
+    // its sums and its accumulators, as they are, into its own LDS region as soon as its own loop is over (the
+    // region held its K/V tiles, which are dead by then; nobody else touches it), so that after the barrier that
+    // waits for the slowest wave only the sums are left to do; the weights exp2(reference - row maximum) are
+    // applied there.
     float* red_m = reinterpret_cast<float*>(smem + L::kMl);  // [kWaves][16 * kMaxMT]
     float* red_l = red_m + kWaves * 16 * kMaxMT;
-    float* red_o = reinterpret_cast<float*>(smem);  // [query tile of the batch][kWaves][16][kRedStride], shares the V tiles' space
+    constexpr int kTileFloats = 16 * kRedStride;  // one query tile of one wave
+    float* red_own = reinterpret_cast<float*>(smem + w * L::kWaveRegion);
     const __amdgpu_buffer_rsrc_t buf_o = partial_buffer(a.part_o), buf_ml = partial_buffer(a.part_ml);
-    __syncthreads();
     if (lg == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -953,27 +959,24 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             red_l[w * 16 * kMaxMT + mt * 16 + li] = l_run[mt];
         }
     }
-    __syncthreads();
-    constexpr int kRedFloats = kWaves * 16 * kRedStride;  // one query tile of all waves in the merge buffer
-    const int w0 = team * kWPT;  // first wave of this wave's team
-#pragma unroll
-    for (int mt0 = 0; mt0 < MT; mt0 += RT) {
+    auto dump_batch = [&](int mt0) {
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
             const int mt = mt0 + r;
             if (mt >= MT) break;
-            float m_star = -INFINITY;
 #pragma unroll
-            for (int ww = 0; ww < kWPT; ++ww) m_star = fmaxf(m_star, red_m[(w0 + ww) * 16 * kMaxMT + mt * 16 + li]);
-            const float m_use = m_star == -INFINITY ? 0.0f : m_star;
-            const float f = fast_exp2(m_run[mt] - m_use) * v_mul;
-#pragma unroll
-            for (int db = 0; db < 8; ++db) {
-                const f32x4 o = acc[mt][db] * f;
-                *reinterpret_cast<f32x4*>(red_o + r * kRedFloats + (w * 16 + li) * kRedStride + db * 16 + 4 * lg) = o;
-            }
+            for (int db = 0; db < 8; ++db)
+                *reinterpret_cast<f32x4*>(red_own + r * kTileFloats + li * kRedStride + db * 16 + 4 * lg) = acc[mt][db];
         }
-        __syncthreads();
+    };
+    dump_batch(0);
+    __syncthreads();
+#pragma unroll
+    for (int mt0 = 0; mt0 < MT; mt0 += RT) {
+        if (mt0 > 0) {
+            dump_batch(mt0);
+            __syncthreads();
+        }
         // 256 threads sum 16 rows x 128 d over the waves of a team: thread -> row tid/16, 8 consecutive d
 #pragma unroll
         for (int tt = 0; tt < TEAMS; ++tt) {
@@ -985,7 +988,6 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
             for (int r = 0; r < RT; ++r) {
                 const int mt = mt0 + r;
                 if (mt >= MT) break;
-                const float* red_t = red_o + r * kRedFloats;
                 const int row = threadIdx.x >> 4, d0 = (threadIdx.x & 15) * 8;
                 const int m = mt * 16 + row;
                 // every LDS read of the tile is sent for before the first sum: one wait instead of one per pair
@@ -994,26 +996,27 @@ __device__ void attend_segment(const FastArgs& a, const Segment& sg, const KVStr
                 float wm[kWPT], wl[kWPT];
 #pragma unroll
                 for (int ww = 0; ww < kWPT; ++ww) {
-                    part0[ww] = *reinterpret_cast<const f32x4*>(red_t + ((ws0 + ww) * 16 + row) * kRedStride + d0);
-                    part1[ww] = *reinterpret_cast<const f32x4*>(red_t + ((ws0 + ww) * 16 + row) * kRedStride + d0 + 4);
+                    const float* red_w = reinterpret_cast<const float*>(smem + (ws0 + ww) * L::kWaveRegion) + r * kTileFloats;
+                    part0[ww] = *reinterpret_cast<const f32x4*>(red_w + row * kRedStride + d0);
+                    part1[ww] = *reinterpret_cast<const f32x4*>(red_w + row * kRedStride + d0 + 4);
                     wm[ww] = red_m[(ws0 + ww) * 16 * kMaxMT + m];
                     wl[ww] = red_l[(ws0 + ww) * 16 * kMaxMT + m];
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                f32x4 s0 = part0[0], s1 = part1[0];
+                float ms = -INFINITY;
 #pragma unroll
-                for (int ww = 1; ww < kWPT; ++ww) {
-                    s0 += part0[ww];
-                    s1 += part1[ww];
+                for (int ww = 0; ww < kWPT; ++ww) ms = fmaxf(ms, wm[ww]);
+                const float mu = ms == -INFINITY ? 0.0f : ms;
+                f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+                float ls = 0.0f;
+#pragma unroll
+                for (int ww = 0; ww < kWPT; ++ww) {
+                    const float e = fast_exp2(wm[ww] - mu);  // weight of the wave's piece (0 for a wave that saw no key of the row)
+                    ls += wl[ww] * e;
+                    s0 += part0[ww] * (e * v_mul);
+                    s1 += part1[ww] * (e * v_mul);
                 }
                 if (m < M_s) {
-                    float ms = -INFINITY;
-#pragma unroll
-                    for (int ww = 0; ww < kWPT; ++ww) ms = fmaxf(ms, wm[ww]);
-                    const float mu = ms == -INFINITY ? 0.0f : ms;
-                    float ls = 0.0f;
-#pragma unroll
-                    for (int ww = 0; ww < kWPT; ++ww) ls += wl[ww] * fast_exp2(wm[ww] - mu);
                     if (final_out) {
                         const int j = j0_s + m / G, h = kvh * G + m % G;
                         const size_t o_idx = ((size_t)(q0 + j) * a.H_q + h) * kD + d0;
