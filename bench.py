@@ -124,10 +124,23 @@ def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=
     def rank_only():  # early-exit check on the step's target rows (stand-ins for intermediate scores); not part of the step
         fsr.topk_rank_check(p_t, toks, cu_q, cu_d, K=10, rank=rank[:int(b.cu_d[-1])], keep_mask=keep)
 
+    calls = dict(accept=accept_only, compact=compact_only, rank=rank_only)
+    if getattr(b, "z_target", None) is not None:  # --logits: the same acceptance from logits (softmax inside the call)
+        z_t, z_d = dev(b.z_target), dev(b.z_draft)
+        ws_lg = torch.empty(max(256, fsr.accept_workspace_bytes(B=b.B, V=b.V, S_max=S_max, mode=1)), dtype=torch.uint8,
+                            device="cuda")
+        acc_l, nem_l, em_l = torch.empty_like(acc), torch.empty_like(nem), torch.empty_like(em)
+
+        def accept_logits_only():  # not part of the step
+            fsr.spec_accept(z_t, z_d, toks, u_a, u_s, cu_q, cu_d, S_max=S_max, mode=1, temperature=1.0, accepted_len=acc_l,
+                            n_emitted=nem_l, emitted=em_l, workspace=ws_lg)
+
+        calls["accept_logits"] = accept_logits_only
+
     state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed,
                  n_caches=n_caches, kv_bytes=kv_bytes, k_caches=k_caches, v_caches=v_caches,
                  dev=dict(bt=bt, ctx=ctx, spec=spec, cu_q=cu_q, cu_d=cu_d, p_t=p_t, p_d=p_d, toks=toks, u_a=u_a, u_s=u_s),
-                 calls=dict(accept=accept_only, compact=compact_only, rank=rank_only))
+                 calls=calls)
     return step, attention_all_layers, tail, state
 
 
@@ -150,7 +163,21 @@ def kernel_figures(b, st, times_us):
         return dict(us=us, launches=launches, algorithmic_bytes=nbytes, achieved_GBs=gbs, frac_of_hbm_peak=gbs / HBM_PEAK_GBS,
                     note=note)
 
+    extra = {}
+    if "accept_logits" in times_us:
+        # LOGITS mode: the rows that have to be normalised are those of the drafts tested (one target and one draft row
+        # each, up to and including the first rejection) and the bonus row; the row(s) sampled from are read once more
+        tested = np.minimum(acc + 1, d)
+        norm_rows = 2 * tested + (acc == d)
+        logits_bytes = int(((norm_rows + rows) * 4 * b.V + 8 * d).sum())
+        all_rows_bytes = int((2 * d + 1).sum()) * 4 * b.V
+        extra["spec_accept_logits"] = fig(
+            times_us["accept_logits"], logits_bytes, 3,
+            "accept_stats_kernel (twice, with a first accept_decide_kernel in between, when the call holds 3072 rows or more) + accept_decide_kernel + "
+            f"accept_sample_kernel, T = 1; normalising every row of the call would read {all_rows_bytes} bytes; "
+            f"not part of the timed step")
     return {
+        **extra,
         "spec_accept": fig(times_us["accept"], accept_bytes, 2, "accept_decide_kernel + accept_sample_kernel"),
         "survivor_compact": fig(times_us["compact"], compact_bytes, 2,
                                 f"prune_scan_kernel + gather_rows_kernel; {n_new} of {b.N} rows of {row_bytes} bytes survive"),
@@ -416,6 +443,8 @@ def main():
     ap.add_argument("--overlap", type=int, default=0, metavar="N",
                     help="also measure the step's attention on a stream that owns all but N compute units next to a "
                          "stand-in drafter on a stream that owns those N (adds an \"overlap\" object to the JSON line)")
+    ap.add_argument("--logits", action="store_true",
+                    help="also time spec_accept in LOGITS mode on the step's rows (reported under kernels.spec_accept_logits)")
     ap.add_argument("--probe", action="store_true", help="time only the plain-read probe (three access patterns) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that hardware byte counters of a "
@@ -436,7 +465,7 @@ def main():
 
     fsr.load_library()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    b = workloads.make_batch(args.workload)
+    b = workloads.make_batch(args.workload, keep_logits=True) if args.logits else workloads.make_batch(args.workload)
     drafts = int(b.spec_lens.sum())
     attn_kernel = "attn_stream_kernel" if args.no_plan else "attn_planned_kernel"
 

@@ -31,6 +31,9 @@ namespace {
 constexpr int kChunk = 4096;        // vocabulary tokens per chunk
 constexpr int kThreads = 256;       // threads per block in stats / partials / select
 constexpr int kPerThread = kChunk / kThreads;  // 16 contiguous tokens per thread in select
+constexpr int kStatGroup = 8;       // LOGITS mode: chunks whose softmax statistics one workgroup folds into one (max, sum) pair
+constexpr int kLazyJ = 2;           // LOGITS mode, two-pass statistics: drafts tested before the rest of a request's rows is normalised
+constexpr int kLazyMinRows = 3072;  // rows a call must be able to hold for the two extra launches of the two passes to pay
 constexpr int kMaxSampleGroup = 8;  // accept_sample: a workgroup takes 1, 2, 4 or 8 consecutive chunks (see launch_all)
 constexpr int kMaxChunksLds = 256;  // chunk masses of a request that the selecting workgroup keeps in LDS (vocabularies up to 2^20)
 
@@ -50,12 +53,14 @@ struct Workspace {
     Decision* dec;       // [B]
     double* mass_res;    // [B, n_chunks]
     double* mass_tgt;    // [B, n_chunks]
-    double* stat_t;      // [R_t_cap, n_chunks, 2]  (LOGITS)
-    double* stat_d;      // [R_d_cap, n_chunks, 2]
+    double* stat_t;      // [R_t_cap, n_stat_groups, 2]  (LOGITS)
+    double* stat_d;      // [R_d_cap, n_stat_groups, 2]
     unsigned int* arrivals;  // [B] chunk workgroups of the request that have finished (zeroed by decide)
+    int* pending;            // [B] (LOGITS, two-phase statistics) the request's first kLazyJ drafts were all accepted and more remain
 };
 
 __host__ __device__ inline int n_chunks_of(int V) { return (V + kChunk - 1) / kChunk; }
+__host__ __device__ inline int n_stat_groups_of(int V) { return (n_chunks_of(V) + kStatGroup - 1) / kStatGroup; }
 
 size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
     const size_t nc = (size_t)n_chunks_of(p.V), B = (size_t)p.B;
@@ -70,9 +75,12 @@ size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
     tmp.mass_res = (double*)take(B * nc * sizeof(double));
     tmp.mass_tgt = (double*)take(B * nc * sizeof(double));
     tmp.arrivals = (unsigned int*)take(B * sizeof(unsigned int));
+    tmp.pending = nullptr;
     if (p.mode == FSR_LOGITS) {
-        tmp.stat_t = (double*)take(B * (size_t)(p.S_max + 1) * nc * 2 * sizeof(double));
-        tmp.stat_d = (double*)take(B * (size_t)p.S_max * nc * 2 * sizeof(double));
+        tmp.pending = (int*)take(B * sizeof(int));
+        const size_t nsg = (size_t)n_stat_groups_of(p.V);
+        tmp.stat_t = (double*)take(B * (size_t)(p.S_max + 1) * nsg * 2 * sizeof(double));
+        tmp.stat_d = (double*)take(B * (size_t)p.S_max * nsg * 2 * sizeof(double));
     } else {
         tmp.stat_t = tmp.stat_d = nullptr;
     }
@@ -99,18 +107,20 @@ __device__ __forceinline__ float to_float(uint16_t x) { return __builtin_bit_cas
 __device__ __forceinline__ bool row_vec_ok(const float* row) { return ((uintptr_t)row & 15) == 0; }
 __device__ __forceinline__ bool row_vec_ok(const uint16_t* row) { return ((uintptr_t)row & 7) == 0; }
 
-// Four consecutive values of a row starting at token e (bounds-checked; vector load when
-// the row is aligned for it).
-__device__ __forceinline__ void load_quad(const float* __restrict__ row, int e, int V, bool vec, float (&x)[4]) {
+// Four consecutive values of a row starting at token e (bounds-checked: `fill` stands for tokens past the
+// vocabulary; vector load when the row is aligned for it).
+__device__ __forceinline__ void load_quad(const float* __restrict__ row, int e, int V, bool vec, float (&x)[4],
+                                          float fill = 0.0f) {
     if (vec && e + 3 < V) {
         const float4 t = *reinterpret_cast<const float4*>(row + e);
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
     } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? row[e + k] : 0.0f;
+        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? row[e + k] : fill;
     }
 }
-__device__ __forceinline__ void load_quad(const uint16_t* __restrict__ row, int e, int V, bool vec, float (&x)[4]) {
+__device__ __forceinline__ void load_quad(const uint16_t* __restrict__ row, int e, int V, bool vec, float (&x)[4],
+                                          float fill = 0.0f) {
     if (vec && e + 3 < V) {
         const uint2 t = *reinterpret_cast<const uint2*>(row + e);
         x[0] = __builtin_bit_cast(float, t.x << 16);
@@ -119,73 +129,184 @@ __device__ __forceinline__ void load_quad(const uint16_t* __restrict__ row, int 
         x[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
     } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? to_float(row[e + k]) : 0.0f;
+        for (int k = 0; k < 4; ++k) x[k] = (e + k < V) ? to_float(row[e + k]) : fill;
     }
 }
 
-// Probability of one entry in fp64: the value itself, or exp(z / T - m) / Z.
+// Constants of exp_softmax, made once per kernel.  The empty asm statements pin each one to a scalar register pair
+// (the leading coefficient to a vector pair) and hide its value from the compiler, which otherwise rebuilds every
+// constant with move instructions in front of each use: that doubles the instruction count of the polynomial.
+struct ExpConsts {
+    double floor, log2e, nln2_hi, nln2_lo, magic, c11, c10, c9, c8, c7, c6, c5, c4, c3;
+};
+__device__ __forceinline__ ExpConsts exp_consts() {
+    ExpConsts k;
+    k.floor = -800.0;  // below it exp is 0 in fp64
+    k.log2e = 1.4426950408889634074;
+    k.nln2_hi = -6.93147180369123816490e-01;  // high part of ln2: 21 significant bits, so k * hi is exact
+    k.nln2_lo = -1.90821492927058770002e-10;
+    k.magic = 6755399441055744.0;  // 1.5 * 2^52: adding it rounds to an integer and leaves that integer in the low word
+    k.c11 = 1.0 / 39916800.0;
+    k.c10 = 1.0 / 3628800.0;
+    k.c9 = 1.0 / 362880.0;
+    k.c8 = 1.0 / 40320.0;
+    k.c7 = 1.0 / 5040.0;
+    k.c6 = 1.0 / 720.0;
+    k.c5 = 1.0 / 120.0;
+    k.c4 = 1.0 / 24.0;
+    k.c3 = 1.0 / 6.0;
+    asm volatile("" : "+s"(k.log2e), "+s"(k.nln2_hi), "+s"(k.nln2_lo), "+v"(k.c11), "+v"(k.magic));
+    asm volatile("" : "+s"(k.c10), "+s"(k.c9), "+s"(k.c8), "+s"(k.c7));
+    asm volatile("" : "+s"(k.c6), "+s"(k.c5), "+s"(k.c4), "+s"(k.c3), "+s"(k.floor));
+    return k;
+}
+
+// exp(x) in fp64 for the arguments a softmax produces (x <= 0 after the row maximum is taken off; x up to a few
+// hundred works too; x below -745, -inf included, gives 0, and so does NaN: such a logit counts as masked).
+// x = k ln2 + r with |r| <= ln2 / 2: k by adding 1.5 * 2^52 to x log2(e), which rounds to the integer and leaves it
+// in the sum's low word; ln2 in two parts so that r is exact to the last bit; exp(r) by its series to degree 11
+// (truncation 6e-15 relative); times 2^k by ldexp, which also makes the subnormal results and the final 0.  17
+// instructions where the library routine, exact to the last bit, takes several times as many: the per-element exp is
+// what bounds the LOGITS-mode kernels, and a decision u q < p or a CDF crossing changes only if it was closer than
+// 1e-14 relative to begin with.  The fused multiply-adds are written out so that each takes its constant straight
+// from a scalar register.
+__device__ __forceinline__ double exp_softmax(double x, const ExpConsts& k) {
+    auto fma_vvs = [](double a, double b, double c) { return fma(a, b, c); };
+    auto fma_vsv = [](double a, double b, double c) { return fma(a, b, c); };
+    x = fmax(x, k.floor);
+    const double t = fma_vsv(x, k.log2e, k.magic);
+    const double kf = t - k.magic;
+    double r = fma_vsv(kf, k.nln2_hi, x);
+    r = fma_vsv(kf, k.nln2_lo, r);
+    double p = fma_vvs(k.c11, r, k.c10);
+    p = fma_vvs(p, r, k.c9);
+    p = fma_vvs(p, r, k.c8);
+    p = fma_vvs(p, r, k.c7);
+    p = fma_vvs(p, r, k.c6);
+    p = fma_vvs(p, r, k.c5);
+    p = fma_vvs(p, r, k.c4);
+    p = fma_vvs(p, r, k.c3);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)(uint32_t)__builtin_bit_cast(unsigned long long, t));
+}
+__device__ __forceinline__ double exp_softmax(double x) { return exp_softmax(x, exp_consts()); }
+// The constants for a kernel of the given mode: PROBS mode never evaluates exp and gets an empty set.
 template <int MODE>
-__device__ __forceinline__ double prob_of(float x, double T, double m, double Z) {
+__device__ __forceinline__ ExpConsts exp_consts_for() {
+    if constexpr (MODE == FSR_LOGITS) return exp_consts();
+    else return ExpConsts{};
+}
+
+// Probability of one entry in fp64: the value itself, or exp(z / T - m) / Z with the two divisions as products
+// by 1 / T and 1 / Z (loop invariants the compiler hoists).  m is a maximum of values z * (1 / T) formed the same
+// way, so the row's largest entry gives exp(0) exactly.
+template <int MODE>
+__device__ __forceinline__ double prob_of(float x, double T, double m, double Z, const ExpConsts& ek) {
     if constexpr (MODE == FSR_PROBS) {
         return (double)x;
     } else {
-        return exp((double)x / T - m) / Z;
+        return exp_softmax((double)x * (1.0 / T) - m, ek) * (1.0 / Z);
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// LOGITS mode: per (row, chunk) max of z/T and sum of exp(z/T - max), fp64.
-// grid = (n_chunks, R_t_cap + R_d_cap)
+// LOGITS mode: per row and group of kStatGroup chunks, the maximum of z / T and the sum of exp(z / T - max), fp64.
+// grid = (n_stat_groups, B * slots): a request owns `slots` consecutive workgroup rows; slot k < t_n is its target
+// row t_lo + k, the others are its draft rows d_lo, d_lo + 1, ...  (which of the request's rows a pass covers is
+// the host's choice: all of them, those of the first kLazyJ drafts, or the rest for the requests left pending).
+// Each lane keeps a running maximum and a sum relative to it over its own elements (16 per chunk), so the chunks of
+// a group need no exchange between lanes; lanes and waves are combined once, at the end.
 // ---------------------------------------------------------------------------------------
 template <typename RT>
 __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
     const RT* __restrict__ z_target, const RT* __restrict__ z_draft, const int32_t* __restrict__ cu_t,
     const int32_t* __restrict__ cu_d, const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows,
-    Workspace ws, int B, int V, int R_t_cap, double T) {
-    __shared__ double smem[kThreads / 64];
-    __shared__ float smax[kThreads / 64];
-    const int c = blockIdx.x, nc = gridDim.x;
-    int r = blockIdx.y;
+    Workspace ws, int B, int V, int S_max, double T, int slots, int t_lo, int t_n, int d_lo, int only_pending) {
+    __shared__ double s_sum[kThreads / 64];
+    __shared__ float s_max[kThreads / 64];
+    const int nc = n_chunks_of(V), nsg = n_stat_groups_of(V);
+    const int i = blockIdx.y / slots, k = blockIdx.y - i * slots;
+    if (only_pending && !ws.pending[i]) return;
     const RT* rows;
     double* stat;
-    if (r < R_t_cap) {
-        if (r >= cu_t[B]) return;
+    if (k < t_n) {
+        const int j = t_lo + k, t0 = cu_t[i], t_i = cu_t[i + 1] - t0;
+        const long long r = (long long)t0 + j;
+        if (j >= t_i || t0 < 0 || r >= (long long)B * (S_max + 1)) return;  // no such row, or past what the workspace holds
         rows = z_target + (size_t)(t_rows ? t_rows[r] : r) * V;
-        stat = ws.stat_t + ((size_t)r * nc + c) * 2;
+        stat = ws.stat_t + ((size_t)r * nsg + blockIdx.x) * 2;
     } else {
-        r -= R_t_cap;
-        if (r >= cu_d[B]) return;
+        const int j = d_lo + (k - t_n), d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
+        const long long r = (long long)d0 + j;
+        if (j >= d_i || d0 < 0 || r >= (long long)B * S_max) return;
         rows = z_draft + (size_t)(d_rows ? d_rows[r] : r) * V;
-        stat = ws.stat_d + ((size_t)r * nc + c) * 2;
+        stat = ws.stat_d + ((size_t)r * nsg + blockIdx.x) * 2;
     }
     const bool vec = row_vec_ok(rows);
-    const int e0 = c * kChunk;
-    float vals[kPerThread];
-    float mx = -INFINITY;
+    const double inv_T = 1.0 / T;
+    const ExpConsts ek = exp_consts();
+    const int c_first = blockIdx.x * kStatGroup, c_end = min(nc, c_first + kStatGroup);
+    float mz = -INFINITY;  // largest logit this lane has seen
+    double mzT = 0.0;      // mz / T once mz is finite
+    double sum = 0.0;      // sum of exp(z / T - mz / T) over this lane's elements
+    // The fold over the group's chunks, twice: for whole chunks of a row aligned for vector loads (four loads per
+    // lane and chunk, all in flight together, the next chunk's issued before this one's arithmetic), and with every
+    // element bounds-checked for the group that holds the vocabulary's ragged end or a row that is not aligned.
+    // Two separate loops, because mixed in one the compiler orders each vector load behind all loads before it.
+    auto fold = [&](auto whole) {
+        float cur[kPerThread], nxt[kPerThread];
+        auto load_chunk = [&](int c, float (&v)[kPerThread]) {
 #pragma unroll
-    for (int k = 0; k < kPerThread / 4; ++k) {
-        const int e = e0 + (k * kThreads + threadIdx.x) * 4;
-        float x[4];
-        load_quad(rows, e, V, vec, x);
+            for (int q = 0; q < kPerThread / 4; ++q) {
+                float x[4];
+                const int e = c * kChunk + (q * kThreads + threadIdx.x) * 4;
+                if constexpr (decltype(whole)::value) load_quad(rows, e, 0x7fffffff, true, x);
+                else load_quad(rows, e, V, vec, x, -INFINITY);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            vals[k * 4 + j] = (e + j < V) ? x[j] : -INFINITY;
-            mx = fmaxf(mx, vals[k * 4 + j]);
+                for (int u = 0; u < 4; ++u) v[q * 4 + u] = x[u];
+            }
+        };
+        load_chunk(c_first, cur);
+        for (int c = c_first; c < c_end; ++c) {
+            if (c + 1 < c_end) load_chunk(c + 1, nxt);
+            float mx = cur[0];
+#pragma unroll
+            for (int u = 1; u < kPerThread; ++u) mx = fmaxf(mx, cur[u]);
+            if (mx > mz) {  // rescale what was summed against the old maximum
+                const double mxT = (double)mx * inv_T;
+                sum = mz == -INFINITY ? 0.0 : sum * exp_softmax(mzT - mxT, ek);
+                mz = mx;
+                mzT = mxT;
+            }
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) sum += exp_softmax((double)cur[u] * inv_T - mzT, ek);  // -inf (masked, or past V) adds 0
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) cur[u] = nxt[u];
         }
+    };
+    if (vec && c_end * kChunk <= V) fold(std::true_type{});
+    else fold(std::false_type{});
+    // lanes -> wave -> workgroup, each time against the common maximum
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const float mw = wave_max(mz);
+    sum = mz == -INFINITY ? 0.0 : sum * exp_softmax(mzT - (double)mw * inv_T, ek);
+    sum = wave_sum(sum);
+    if (lane == 0) {
+        s_max[w] = mw;
+        s_sum[w] = sum;
     }
-    mx = wave_max(mx);
-    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = mx;
     __syncthreads();
-    mx = fmaxf(fmaxf(smax[0], smax[1]), fmaxf(smax[2], smax[3]));
-    const double m = (double)mx / T;  // max of z/T (T > 0): division is monotone
-    double s = 0.0;
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k)
-        if (vals[k] != -INFINITY) s += exp((double)vals[k] / T - m);
-    s = block_sum(s, smem);
     if (threadIdx.x == 0) {
-        stat[0] = m;
-        stat[1] = s;
+        const float mg = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+        const double mgT = (double)mg * inv_T;
+        double tot = 0.0;
+#pragma unroll
+        for (int q = 0; q < kThreads / 64; ++q)
+            if (s_max[q] != -INFINITY) tot += s_sum[q] * exp_softmax((double)s_max[q] * inv_T - mgT, ek);
+        stat[0] = mgT;  // -inf for a group of masked logits only
+        stat[1] = tot;
     }
 }
 
@@ -197,7 +318,7 @@ __device__ __forceinline__ void combine_stats(const double* __restrict__ stat, i
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mm = fmax(mm, __shfl_xor(mm, o, 64));
     double z = 0.0;
-    for (int c = lane; c < nc; c += 64) z += stat[c * 2 + 1] * exp(stat[c * 2] - mm);
+    for (int c = lane; c < nc; c += 64) z += stat[c * 2 + 1] * exp_softmax(stat[c * 2] - mm);
     m = mm;
     Z = wave_sum(z);
 }
@@ -206,7 +327,7 @@ __device__ __forceinline__ void combine_stats_lane(const double* __restrict__ st
     double mm = -INFINITY;
     for (int c = 0; c < nc; ++c) mm = fmax(mm, stat[c * 2]);
     double z = 0.0;
-    for (int c = 0; c < nc; ++c) z += stat[c * 2 + 1] * exp(stat[c * 2] - mm);
+    for (int c = 0; c < nc; ++c) z += stat[c * 2 + 1] * exp_softmax(stat[c * 2] - mm);
     m = mm;
     Z = z;
 }
@@ -215,17 +336,17 @@ __device__ __forceinline__ void combine_stats_lane(const double* __restrict__ st
 template <int MODE, typename RT>
 __device__ __forceinline__ void quad_masses(const Decision& dec, const RT* __restrict__ trow,
                                             const RT* __restrict__ drow, int e, int V, bool vec_t, bool vec_d,
-                                            double T, double (&res)[4], double (&tgt)[4]) {
+                                            double T, const ExpConsts& ek, double (&res)[4], double (&tgt)[4]) {
     float a[4], b[4];
     load_quad(trow, e, V, vec_t, a);
     if (dec.kind == kCaseResidual) load_quad(drow, e, V, vec_d, b);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const bool ok = e + k < V;
-        const double pt = ok ? prob_of<MODE>(a[k], T, dec.m_t, dec.Z_t) : 0.0;
+        const double pt = ok ? prob_of<MODE>(a[k], T, dec.m_t, dec.Z_t, ek) : 0.0;
         tgt[k] = pt;
         if (dec.kind == kCaseResidual) {
-            const double qd = ok ? prob_of<MODE>(b[k], T, dec.m_d, dec.Z_d) : 0.0;
+            const double qd = ok ? prob_of<MODE>(b[k], T, dec.m_d, dec.Z_d, ek) : 0.0;
             const double r = pt - qd;
             res[k] = r > 0.0 ? r : 0.0;
         } else {
@@ -256,14 +377,18 @@ __device__ __forceinline__ double fetch_f64(const double* p) {
 // ---------------------------------------------------------------------------------------
 // decide: one wave per request; lane n tests draft n.
 // ---------------------------------------------------------------------------------------
-template <int MODE, typename RT>
+// PHASE 0: all drafts.  PHASE 1 (LOGITS, two-phase statistics): only the first kLazyJ drafts; a request whose first
+// kLazyJ drafts are all accepted and that has more is left pending, everything else is final.  PHASE 2: the pending
+// requests, from the start, now that all their rows are normalised.
+template <int MODE, typename RT, int PHASE>
 __global__ __launch_bounds__(64) void accept_decide_kernel(
     const RT* __restrict__ p_target, const RT* __restrict__ p_draft, const int32_t* __restrict__ draft_tokens,
     const float* __restrict__ u_accept, const int32_t* __restrict__ cu_t, const int32_t* __restrict__ cu_d,
     const int32_t* __restrict__ t_rows, const int32_t* __restrict__ d_rows, int32_t* __restrict__ accepted_len,
     int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
     const int i = blockIdx.x, lane = threadIdx.x;
-    const int nc = n_chunks_of(V);
+    if (PHASE == 2 && !ws.pending[i]) return;
+    const int nsg = n_stat_groups_of(V);
     const int t0 = cu_t[i], t_i = cu_t[i + 1] - t0, d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
     Decision dec;
@@ -282,13 +407,16 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
             accepted_len[i] = -1;
             n_emitted[i] = -1;
             ws.dec[i] = dec;
+            if (PHASE == 1) ws.pending[i] = 0;
         }
         return;
     }
-    int n = d_i;  // accepted drafts
-    for (int n0 = 0; n0 < d_i && n == d_i; n0 += 64) {
+    const int d_lim = PHASE == 1 ? min(d_i, kLazyJ) : d_i;  // drafts this pass tests
+    const ExpConsts ek = exp_consts_for<MODE>();
+    int n = d_lim;  // accepted drafts
+    for (int n0 = 0; n0 < d_lim && n == d_lim; n0 += 64) {
         const int k = n0 + lane;
-        const bool live = k < d_i;
+        const bool live = k < d_lim;
         long long tr = 0, dr = 0;
         double m_t = 0.0, Z_t = 1.0, m_d = 0.0, Z_d = 1.0;
         int x = 0;
@@ -299,11 +427,11 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
             x = min(max(draft_tokens[dr], 0), V - 1);
             const double u = (double)u_accept[dr];
             if constexpr (MODE == FSR_LOGITS) {
-                combine_stats_lane(ws.stat_t + (size_t)(t0 + k) * nc * 2, nc, m_t, Z_t);
-                combine_stats_lane(ws.stat_d + (size_t)(d0 + k) * nc * 2, nc, m_d, Z_d);
+                combine_stats_lane(ws.stat_t + (size_t)(t0 + k) * nsg * 2, nsg, m_t, Z_t);
+                combine_stats_lane(ws.stat_d + (size_t)(d0 + k) * nsg * 2, nsg, m_d, Z_d);
             }
-            const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t);
-            const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d);
+            const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t, ek);
+            const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d, ek);
             ok = u * qx < px;
         }
         const unsigned long long rejected = __builtin_amdgcn_ballot_w64(live && !ok);
@@ -318,11 +446,16 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
             dec.m_d = shfl_f64(m_d, first); dec.Z_d = shfl_f64(Z_d, first);
         }
     }
+    if (PHASE == 1) {
+        const bool pending = n == d_lim && d_i > d_lim;  // nothing rejected so far and drafts remain
+        if (lane == 0) ws.pending[i] = pending ? 1 : 0;
+        if (pending) return;
+    }
     dec.n = n;
     if (n == d_i && t_i == d_i + 1) {
         dec.kind = kCaseTarget;
         dec.t_row = t_rows ? t_rows[t0 + d_i] : t0 + d_i;
-        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nc * 2, nc, dec.m_t, dec.Z_t);
+        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nsg * 2, nsg, dec.m_t, dec.Z_t);
     }
     for (int s = n + lane; s <= S_max; s += 64) em[s] = -1;
     if (lane == 0) {
@@ -347,6 +480,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     __shared__ int s_chunk, s_fallback, s_last;
     __shared__ double s_mass[2 * kMaxChunksLds];
     const int nc = n_chunks_of(V), i = blockIdx.y;
+    const ExpConsts ek = exp_consts_for<MODE>();
     const int c_first = blockIdx.x * kSampleGroup, n_here = min(kSampleGroup, nc - c_first);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
@@ -371,7 +505,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
                 for (int k = 0; k < kPerThread / 4; ++k) {
                     const int e = e0 + (k * kThreads + threadIdx.x) * 4;
                     double res[4], tgt[4];
-                    quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, res, tgt);
+                    quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, ek, res, tgt);
                     sr[cc] += (res[0] + res[1]) + (res[2] + res[3]);
                     st[cc] += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
                 }
@@ -472,7 +606,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
 #pragma unroll
     for (int k = 0; k < kPerThread / 4; ++k) {
         double res[4], tgt[4];
-        quad_masses<MODE, RT>(dec, trow, drow, e0 + 4 * k, V, vec_t, vec_d, T, res, tgt);
+        quad_masses<MODE, RT>(dec, trow, drow, e0 + 4 * k, V, vec_t, vec_d, T, ek, res, tgt);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             mass[4 * k + j] = res[j];
@@ -519,14 +653,37 @@ int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_token
     const int nc = n_chunks_of(p.V);
     const double T = p.temperature;
     int rc;
+#define FSR_DECIDE(PHASE)                                                                                                    \
+    hipLaunchKernelGGL((accept_decide_kernel<MODE, RT, PHASE>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, \
+                       cu_t, cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T)
     if (MODE == FSR_LOGITS) {
-        const int R_t_cap = p.B * (p.S_max + 1), R_d_cap = p.B * p.S_max;
-        hipLaunchKernelGGL(accept_stats_kernel<RT>, dim3(nc, R_t_cap + R_d_cap), dim3(kThreads), 0, s, p_target, p_draft, cu_t,
-                           cu_d, t_rows, d_rows, ws, p.B, p.V, R_t_cap, T);
-        if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
+        const int rows_cap = p.B * (2 * p.S_max + 1), nsg = n_stat_groups_of(p.V);
+    // rows of a request one pass covers: target rows T_LO .. T_LO + T_N - 1 and draft rows D_LO .. D_LO + D_N - 1
+#define FSR_STATS(T_LO, T_N, D_LO, D_N, ONLY_PENDING)                                                                        \
+    hipLaunchKernelGGL(accept_stats_kernel<RT>, dim3(nsg, p.B * ((T_N) + (D_N))), dim3(kThreads), 0, s, p_target, p_draft, cu_t, \
+                       cu_d, t_rows, d_rows, ws, p.B, p.V, p.S_max, T, (T_N) + (D_N), T_LO, T_N, D_LO, ONLY_PENDING)
+        // Only rows 0..n of a request (n = accepted drafts) have to be normalised.  With enough rows in the call to be
+        // worth two more launches, the rows the first kLazyJ drafts need are normalised and those drafts tested first;
+        // the remaining rows are read only for the requests that accepted all of them.
+        const bool two_phase = p.S_max > kLazyJ + 1 && rows_cap >= kLazyMinRows;
+        if (two_phase) {
+            FSR_STATS(0, kLazyJ + 1, 0, kLazyJ, 0);
+            if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
+            FSR_DECIDE(1);
+            if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
+            FSR_STATS(kLazyJ + 1, p.S_max - kLazyJ, kLazyJ, p.S_max - kLazyJ, 1);
+            if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
+            FSR_DECIDE(2);
+        } else {
+            FSR_STATS(0, p.S_max + 1, 0, p.S_max, 0);
+            if ((rc = check_launch("accept_stats_kernel")) != FSR_OK) return rc;
+            FSR_DECIDE(0);
+        }
+#undef FSR_STATS
+    } else {
+        FSR_DECIDE(0);
     }
-    hipLaunchKernelGGL((accept_decide_kernel<MODE, RT>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, cu_t,
-                       cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T);
+#undef FSR_DECIDE
     if ((rc = check_launch("accept_decide_kernel")) != FSR_OK) return rc;
     // chunks per workgroup: as many as leave the device about four workgroups per compute unit (a small batch
     // keeps one chunk per workgroup: there the call is a latency chain and parallelism is what shortens it)

@@ -125,6 +125,45 @@ def test_logits_mode(fsr, oracle, T):
     assert mism == 0
 
 
+@pytest.mark.parametrize("draft_mode", ["independent", "noise", "equal"])
+@pytest.mark.parametrize("T", [1.0, 0.8])
+def test_logits_mode_with_enough_rows_for_two_passes(fsr, oracle, draft_mode, T):
+    """A call with room for several thousand rows: the library normalises the rows of the first two drafts, tests them, and
+    reads the later rows only of the requests still undecided.  Requests rejected at draft 0, 1, 2 and later, requests
+    accepted whole, with 0, 1, 2 and 3 drafts, with and without a bonus row, and rows reached through maps."""
+    announce(f"accept LOGITS two passes {draft_mode} T={T}")
+    B = 189
+    spec = np.array(([0, 1, 2, 3, 4, 5, 6, 7, 8] * 21), np.int32)
+    b = workloads.make_batch(2, rep=11, with_kv=False, V=33001, B=B, spec_lens=spec.tolist(), ctx_lens=[10] * B,
+                             keep_logits=True, draft_mode=draft_mode)
+    (frag, mism), ref = run_pair(fsr, oracle, b, mode=1, temperature=T)
+    assert mism == 0
+    n = ref["accepted_len"]
+    if draft_mode == "equal":
+        assert np.array_equal(n, spec)
+    else:
+        assert {0, 1, 2} <= set(n[spec >= 4].tolist()) or draft_mode == "noise"
+        assert (n[spec >= 4] >= 3).any() or draft_mode == "independent"
+    # odd requests lose their bonus row; rows shuffled in storage
+    rng = np.random.default_rng(1)
+    perm_t, perm_d = rng.permutation(b.N), rng.permutation(b.N_d)
+    z_t = np.empty_like(b.z_target); z_t[perm_t] = b.z_target
+    z_d = np.empty_like(b.z_draft); z_d[perm_d] = b.z_draft
+    toks = np.empty_like(b.draft_tokens); toks[perm_d] = b.draft_tokens
+    u_a = np.empty_like(b.u_accept); u_a[perm_d] = b.u_accept
+    t_lens = spec + 1 - (np.arange(B) % 2)
+    t_lens[spec == 0] = 1
+    cu_t = workloads.exclusive_offsets(t_lens)
+    t_rows = np.concatenate([perm_t[b.cu_q[i]: b.cu_q[i] + t_lens[i]] for i in range(B)]).astype(np.int32)
+    kw = dict(S_max=b.S_max, mode=1, temperature=T)
+    ref = oracle.spec_accept(z_t, z_d, toks, u_a, b.u_sample, cu_t, b.cu_d, t_rows=t_rows, d_rows=perm_d.astype(np.int32), **kw)
+    gpu = fsr.spec_accept(dev(z_t), dev(z_d), dev(toks), dev(u_a), dev(b.u_sample), dev(cu_t), dev(b.cu_d),
+                          t_rows=dev(t_rows), d_rows=dev(perm_d.astype(np.int32)), **kw)
+    torch.cuda.synchronize()
+    frag, mism = check_accept(gpu, ref, b.u_sample)
+    assert mism == 0
+
+
 def test_invalid_request_is_flagged_not_faulted(fsr, oracle):
     announce("accept invalid request")
     b = workloads.make_batch(1, with_kv=False)
