@@ -31,7 +31,7 @@ namespace {
 constexpr int kChunk = 4096;        // vocabulary tokens per chunk
 constexpr int kThreads = 256;       // threads per block in stats / partials / select
 constexpr int kPerThread = kChunk / kThreads;  // 16 contiguous tokens per thread in select
-constexpr int kStatGroup = 8;       // LOGITS mode: chunks whose softmax statistics one workgroup folds into one (max, sum) pair
+constexpr int kMaxStatGroup = 8;    // LOGITS mode: most chunks whose softmax statistics one workgroup folds into one (max, sum) pair
 constexpr int kLazyJ = 2;           // LOGITS mode, two-pass statistics: drafts tested before the rest of a request's rows is normalised
 constexpr int kLazyMinRows = 3072;  // rows a call must be able to hold for the two extra launches of the two passes to pay
 constexpr int kMaxSampleGroup = 8;  // accept_sample: a workgroup takes 1, 2, 4 or 8 consecutive chunks (see launch_all)
@@ -56,11 +56,12 @@ struct Workspace {
     double* stat_t;      // [R_t_cap, n_stat_groups, 2]  (LOGITS)
     double* stat_d;      // [R_d_cap, n_stat_groups, 2]
     unsigned int* arrivals;  // [B] chunk workgroups of the request that have finished (zeroed by decide)
+    int stat_group;          // chunks per (max, sum) pair in this call (set at launch)
     int* pending;            // [B] (LOGITS, two-phase statistics) the request's first kLazyJ drafts were all accepted and more remain
 };
 
 __host__ __device__ inline int n_chunks_of(int V) { return (V + kChunk - 1) / kChunk; }
-__host__ __device__ inline int n_stat_groups_of(int V) { return (n_chunks_of(V) + kStatGroup - 1) / kStatGroup; }
+__host__ __device__ inline int n_stat_groups_of(int V, int group) { return (n_chunks_of(V) + group - 1) / group; }
 
 size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
     const size_t nc = (size_t)n_chunks_of(p.V), B = (size_t)p.B;
@@ -76,9 +77,10 @@ size_t carve(const fsr_accept_params& p, char* base, Workspace* w) {
     tmp.mass_tgt = (double*)take(B * nc * sizeof(double));
     tmp.arrivals = (unsigned int*)take(B * sizeof(unsigned int));
     tmp.pending = nullptr;
+    tmp.stat_group = kMaxStatGroup;
     if (p.mode == FSR_LOGITS) {
         tmp.pending = (int*)take(B * sizeof(int));
-        const size_t nsg = (size_t)n_stat_groups_of(p.V);
+        const size_t nsg = nc;  // room for one pair per chunk; a call folds 1, 2, 4 or 8 chunks into a pair
         tmp.stat_t = (double*)take(B * (size_t)(p.S_max + 1) * nsg * 2 * sizeof(double));
         tmp.stat_d = (double*)take(B * (size_t)p.S_max * nsg * 2 * sizeof(double));
     } else {
@@ -210,7 +212,7 @@ __device__ __forceinline__ double prob_of(float x, double T, double m, double Z,
 }
 
 // ---------------------------------------------------------------------------------------
-// LOGITS mode: per row and group of kStatGroup chunks, the maximum of z / T and the sum of exp(z / T - max), fp64.
+// LOGITS mode: per row and group of ws.stat_group chunks, the maximum of z / T and the sum of exp(z / T - max), fp64.
 // grid = (n_stat_groups, B * slots): a request owns `slots` consecutive workgroup rows; slot k < t_n is its target
 // row t_lo + k, the others are its draft rows d_lo, d_lo + 1, ...  (which of the request's rows a pass covers is
 // the host's choice: all of them, those of the first kLazyJ drafts, or the rest for the requests left pending).
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
     Workspace ws, int B, int V, int S_max, double T, int slots, int t_lo, int t_n, int d_lo, int only_pending) {
     __shared__ double s_sum[kThreads / 64];
     __shared__ float s_max[kThreads / 64];
-    const int nc = n_chunks_of(V), nsg = n_stat_groups_of(V);
+    const int nc = n_chunks_of(V), nsg = n_stat_groups_of(V, ws.stat_group);
     const int i = blockIdx.y / slots, k = blockIdx.y - i * slots;
     if (only_pending && !ws.pending[i]) return;
     const RT* rows;
@@ -245,15 +247,15 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
     const bool vec = row_vec_ok(rows);
     const double inv_T = 1.0 / T;
     const ExpConsts ek = exp_consts();
-    const int c_first = blockIdx.x * kStatGroup, c_end = min(nc, c_first + kStatGroup);
+    const int c_first = blockIdx.x * ws.stat_group, c_end = min(nc, c_first + ws.stat_group);
     float mz = -INFINITY;  // largest logit this lane has seen
     double mzT = 0.0;      // mz / T once mz is finite
     double sum = 0.0;      // sum of exp(z / T - mz / T) over this lane's elements
     // The fold over the group's chunks, twice: for whole chunks of a row aligned for vector loads (four loads per
     // lane and chunk, all in flight together, the next chunk's issued before this one's arithmetic), and with every
-    // element bounds-checked for the group that holds the vocabulary's ragged end or a row that is not aligned.
+    // element bounds-checked for the chunk that holds the vocabulary's ragged end or a row that is not aligned.
     // Two separate loops, because mixed in one the compiler orders each vector load behind all loads before it.
-    auto fold = [&](auto whole) {
+    auto fold = [&](auto whole, int c_lo, int c_hi) {
         float cur[kPerThread], nxt[kPerThread];
         auto load_chunk = [&](int c, float (&v)[kPerThread]) {
 #pragma unroll
@@ -266,9 +268,10 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
                 for (int u = 0; u < 4; ++u) v[q * 4 + u] = x[u];
             }
         };
-        load_chunk(c_first, cur);
-        for (int c = c_first; c < c_end; ++c) {
-            if (c + 1 < c_end) load_chunk(c + 1, nxt);
+        if (c_lo >= c_hi) return;
+        load_chunk(c_lo, cur);
+        for (int c = c_lo; c < c_hi; ++c) {
+            if (c + 1 < c_hi) load_chunk(c + 1, nxt);
             float mx = cur[0];
 #pragma unroll
             for (int u = 1; u < kPerThread; ++u) mx = fmaxf(mx, cur[u]);
@@ -284,8 +287,9 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
             for (int u = 0; u < kPerThread; ++u) cur[u] = nxt[u];
         }
     };
-    if (vec && c_end * kChunk <= V) fold(std::true_type{});
-    else fold(std::false_type{});
+    const int c_whole = vec ? min(c_end, V / kChunk) : c_first;  // chunks before it are whole and aligned
+    fold(std::true_type{}, c_first, c_whole);
+    fold(std::false_type{}, max(c_first, c_whole), c_end);
     // lanes -> wave -> workgroup, each time against the common maximum
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const float mw = wave_max(mz);
@@ -386,7 +390,7 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
     int32_t* __restrict__ n_emitted, int32_t* __restrict__ emitted, Workspace ws, int B, int V, int S_max, double T) {
     const int i = blockIdx.x, lane = threadIdx.x;
     if (PHASE == 2 && !ws.pending[i]) return;
-    const int nsg = n_stat_groups_of(V);
+    const int nsg = n_stat_groups_of(V, ws.stat_group);
     const int t0 = cu_t[i], t_i = cu_t[i + 1] - t0, d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
     Decision dec;
@@ -647,7 +651,8 @@ template <int MODE, typename RT>
 int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_tokens, const float* u_accept,
                const float* u_sample, const int32_t* cu_t, const int32_t* cu_d, const int32_t* t_rows,
                const int32_t* d_rows, int32_t* accepted_len, int32_t* n_emitted, int32_t* emitted,
-               const fsr_accept_params& p, const Workspace& ws, hipStream_t s) {
+               const fsr_accept_params& p, const Workspace& ws_in, hipStream_t s) {
+    Workspace ws = ws_in;
     const int nc = n_chunks_of(p.V);
     const double T = p.temperature;
     int rc;
@@ -655,7 +660,13 @@ int launch_all(const RT* p_target, const RT* p_draft, const int32_t* draft_token
     hipLaunchKernelGGL((accept_decide_kernel<MODE, RT, PHASE>), dim3(p.B), dim3(64), 0, s, p_target, p_draft, draft_tokens, u_accept, \
                        cu_t, cu_d, t_rows, d_rows, accepted_len, n_emitted, emitted, ws, p.B, p.V, p.S_max, T)
     if (MODE == FSR_LOGITS) {
-        const int rows_cap = p.B * (2 * p.S_max + 1), nsg = n_stat_groups_of(p.V);
+        const int rows_cap = p.B * (2 * p.S_max + 1);
+        // chunks per workgroup: as many as leave the device a few thousand workgroups (a small call is a latency
+        // chain per workgroup, and more of them in parallel is what shortens it)
+        int sg = kMaxStatGroup;
+        while (sg > 1 && (long long)rows_cap * n_stat_groups_of(p.V, sg) < 4096) sg >>= 1;
+        ws.stat_group = sg;
+        const int nsg = n_stat_groups_of(p.V, sg);
     // rows of a request one pass covers: target rows T_LO .. T_LO + T_N - 1 and draft rows D_LO .. D_LO + D_N - 1
 #define FSR_STATS(T_LO, T_N, D_LO, D_N, ONLY_PENDING)                                                                        \
     hipLaunchKernelGGL(accept_stats_kernel<RT>, dim3(nsg, p.B * ((T_N) + (D_N))), dim3(kThreads), 0, s, p_target, p_draft, cu_t, \
