@@ -171,10 +171,17 @@ def kernel_figures(b, st, times_us):
         norm_rows = 2 * tested + (acc == d)
         logits_bytes = int(((norm_rows + rows) * 4 * b.V + 8 * d).sum())
         all_rows_bytes = int((2 * d + 1).sum()) * 4 * b.V
+        if b.B * (2 * b.S_max + 1) >= 3072 and b.S_max > 3:  # two passes: rows of the first two drafts, then the rest of the undecided
+            pend = (np.minimum(acc, 2) == np.minimum(d, 2)) & (d > 2)
+            read_rows = np.minimum(d + 1, 3) + np.minimum(d, 2) + pend * ((d + 1 - 3) + (d - 2))
+        else:
+            read_rows = 2 * d + 1
+        read_bytes = int(((read_rows + rows) * 4 * b.V).sum())
         extra["spec_accept_logits"] = fig(
             times_us["accept_logits"], logits_bytes, 3,
             "accept_stats_kernel (twice, with a first accept_decide_kernel in between, when the call holds 3072 rows or more) + accept_decide_kernel + "
             f"accept_sample_kernel, T = 1; normalising every row of the call would read {all_rows_bytes} bytes; "
+            f"this call reads {read_bytes} bytes; "
             f"not part of the timed step")
     return {
         **extra,
