@@ -164,6 +164,41 @@ def test_logits_mode_with_enough_rows_for_two_passes(fsr, oracle, draft_mode, T)
     assert mism == 0
 
 
+@pytest.mark.parametrize("B", [12, 189])
+@pytest.mark.parametrize("T", [1.0, 0.05])
+def test_logits_mode_masked_vocabulary_and_sharp_temperature(fsr, oracle, B, T):
+    """Logits with half the vocabulary masked to -inf (the target's mask differs from the draft's, so some drafted
+    tokens have target probability exactly 0 and must be rejected, and the residual is 0 wherever both are masked), at
+    T = 1 and at a temperature that puts exp's argument hundreds below zero; one pass (B = 12) and two (B = 189)."""
+    announce(f"accept LOGITS masked B={B} T={T}")
+    spec = np.array(([0, 1, 2, 3, 4, 5, 6, 7, 8] * 21)[:B], np.int32)
+    V = 20011
+    b = workloads.make_batch(2, rep=13, with_kv=False, V=V, B=B, spec_lens=spec.tolist(), ctx_lens=[10] * B,
+                             keep_logits=True, draft_mode="noise")
+    rng = np.random.default_rng(5)
+    z_t, z_d = b.z_target.copy(), b.z_draft.copy()
+    mask_d = rng.random((b.N_d, V)) < 0.5
+    mask_d[np.arange(b.N_d), b.draft_tokens] = False          # a drafted token has positive draft probability
+    z_d[mask_d] = -np.inf
+    mask_t = rng.random((b.N, V)) < 0.5
+    mask_t[np.arange(b.N), rng.integers(0, V, b.N)] = False    # no target row is masked entirely
+    z_t[mask_t] = -np.inf
+    kw = dict(S_max=b.S_max, mode=1, temperature=T)
+    ref = oracle.spec_accept(z_t, z_d, b.draft_tokens, b.u_accept, b.u_sample, b.cu_q, b.cu_d, **kw)
+    gpu = fsr.spec_accept(dev(z_t), dev(z_d), dev(b.draft_tokens), dev(b.u_accept), dev(b.u_sample), dev(b.cu_q),
+                          dev(b.cu_d), **kw)
+    torch.cuda.synchronize()
+    frag, mism = check_accept(gpu, ref, b.u_sample)
+    print(f"masked LOGITS B={B} T={T}: fragile={frag} mismatches={mism} accepted={ref['accepted_len'].sum()}/{b.N_d}")
+    assert mism == 0
+    # no emitted token is one the target masks at its position
+    em, n = ref["emitted"], ref["accepted_len"]
+    for i in range(B):
+        for k in range(ref["n_emitted"][i]):
+            assert not mask_t[b.cu_q[i] + k, em[i, k]]
+    assert 0 < n.sum() < b.N_d
+
+
 def test_invalid_request_is_flagged_not_faulted(fsr, oracle):
     announce("accept invalid request")
     b = workloads.make_batch(1, with_kv=False)
