@@ -288,6 +288,11 @@ int fsr_accept_workspace_bytes(const fsr_accept_params* p /*host*/, size_t* out_
  *   accepted_len [B] int32 (n), n_emitted [B] int32, emitted [B, S_max+1] int32 padded -1
  * Requests with d_i > S_max or t_i - d_i outside {0,1} get accepted_len = n_emitted = -1.
  * Draft token ids are clamped into [0, V).
+ * FSR_LOGITS mode: p = softmax(z / temperature) with sums in fp64 and an exponential good
+ * to 5e-16 relative; a logit of -inf (a masked token) has probability exactly 0, a NaN
+ * logit is treated the same way; a row needs at least one finite logit.  Only the rows
+ * the outcome depends on are guaranteed to be read (target rows 0 .. n and draft rows
+ * 0 .. min(n, d_i - 1)); a large call skips the later rows of requests rejected early.
  *
  * FSR_GREEDY mode (the same rule at temperature 0): draft n is accepted iff it equals the
  * arg-max token of target row n (the lowest id among equal maxima); the token after the

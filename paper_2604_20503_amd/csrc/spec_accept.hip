@@ -8,7 +8,10 @@
 // Work split.  A verification batch has few requests (16 .. 512) but a vocabulary of
 // ~1.3e5, so one workgroup per request cannot fill the chip: every vocabulary row is cut
 // into chunks of kChunk tokens and the vocabulary-wide sums are two-level.
-//   stats    (LOGITS mode only) per (row, chunk): max and sum of exp in fp64
+//   stats    (LOGITS mode only) per row and group of 1-8 chunks: max of z / T and sum of exp(z / T - max) in
+//            fp64.  A large call takes two passes: the rows the first kLazyJ drafts of every request need,
+//            a first `decide` on those drafts, then the remaining rows of the requests still undecided and
+//            `decide` once more for those (only rows 0 .. n of a request, n = accepted drafts, are needed)
 //   decide   per request, one wave: the accept tests, one lane per draft with all gathers in flight
 //            together; picks the row pair to sample from and records it
 //   sample   grid (chunks, requests): every workgroup sums the fp64 mass of its chunk of the residual
@@ -57,7 +60,7 @@ struct Workspace {
     double* stat_d;      // [R_d_cap, n_stat_groups, 2]
     unsigned int* arrivals;  // [B] chunk workgroups of the request that have finished (zeroed by decide)
     int stat_group;          // chunks per (max, sum) pair in this call (set at launch)
-    int* pending;            // [B] (LOGITS, two-phase statistics) the request's first kLazyJ drafts were all accepted and more remain
+    int* pending;            // [B] (LOGITS, two-pass statistics) the request's first kLazyJ drafts were all accepted and more remain
 };
 
 __host__ __device__ inline int n_chunks_of(int V) { return (V + kChunk - 1) / kChunk; }
