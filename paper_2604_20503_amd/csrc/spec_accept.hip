@@ -138,6 +138,19 @@ __device__ __forceinline__ void load_quad(const uint16_t* __restrict__ row, int 
     }
 }
 
+// The same where the caller has checked that the row is aligned and the four tokens exist: the load and nothing else.
+__device__ __forceinline__ void load_quad_vec(const float* __restrict__ row, int e, float (&x)[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(row + e);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+__device__ __forceinline__ void load_quad_vec(const uint16_t* __restrict__ row, int e, float (&x)[4]) {
+    const uint2 t = *reinterpret_cast<const uint2*>(row + e);
+    x[0] = __builtin_bit_cast(float, t.x << 16);
+    x[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
+    x[2] = __builtin_bit_cast(float, t.y << 16);
+    x[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
+}
+
 // Constants of exp_softmax, made once per kernel.  The empty asm statements pin each one to a scalar register pair
 // (the leading coefficient to a vector pair) and hide its value from the compiler, which otherwise rebuilds every
 // constant with move instructions in front of each use: that doubles the instruction count of the polynomial.
@@ -265,7 +278,7 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
             for (int q = 0; q < kPerThread / 4; ++q) {
                 float x[4];
                 const int e = c * kChunk + (q * kThreads + threadIdx.x) * 4;
-                if constexpr (decltype(whole)::value) load_quad(rows, e, 0x7fffffff, true, x);
+                if constexpr (decltype(whole)::value) load_quad_vec(rows, e, x);
                 else load_quad(rows, e, V, vec, x, -INFINITY);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) v[q * 4 + u] = x[u];
@@ -337,7 +350,7 @@ __device__ __forceinline__ void combine_stats_lane(const double* __restrict__ st
     Z = z;
 }
 
-// Masses of 4 consecutive tokens starting at e for the request's decision.
+// Masses of 4 consecutive tokens starting at e for the request's decision (bounds-checked).
 template <int MODE, typename RT>
 __device__ __forceinline__ void quad_masses(const Decision& dec, const RT* __restrict__ trow,
                                             const RT* __restrict__ drow, int e, int V, bool vec_t, bool vec_d,
@@ -490,6 +503,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int32_t* em = emitted + (size_t)i * (S_max + 1);
     Decision dec = ws.dec[i];
+    dec.kind = __builtin_amdgcn_readfirstlane(dec.kind);  // the same in every lane: say so, branches on it stay scalar
     if (dec.kind == kCaseNone) return;
 
     // ---- 2. fp64 mass of this chunk of the sampling distribution (and of the target row, for the fallback)
@@ -500,32 +514,79 @@ __global__ __launch_bounds__(kThreads) void accept_sample_kernel(
     // row loads, reduction, store-through, arrival count) is paid once per 128 KB instead of once per 32 KB.  Each
     // chunk's mass is reduced exactly as if it had a workgroup to itself (thread sums, wave sums, waves in order).
     {
-        double sr[kSampleGroup], st[kSampleGroup];
-#pragma unroll
-        for (int cc = 0; cc < kSampleGroup; ++cc) {
-            sr[cc] = st[cc] = 0.0;
-            if (cc < n_here) {
-                const int e0 = (c_first + cc) * kChunk;
+        // whole chunks of aligned rows first, through code that has only vector loads (the next chunk's issued before
+        // this chunk's arithmetic); then the chunk with the vocabulary's ragged end (or every chunk, if a row is not
+        // aligned), bounds-checked.  A chunk's two masses go to LDS as soon as the wave has them.
+        const bool vec_ok = vec_t && (dec.kind != kCaseResidual || vec_d);
+        const int n_whole = vec_ok ? min(n_here, max(0, V / kChunk - c_first)) : 0;
+        const bool residual = dec.kind == kCaseResidual;
+        if (n_whole > 0) {
+            float ta[kPerThread], da[kPerThread], tb[kPerThread], db[kPerThread];
+            auto load_rows = [&](int c, float (&t)[kPerThread], float (&d)[kPerThread]) {
 #pragma unroll
                 for (int k = 0; k < kPerThread / 4; ++k) {
-                    const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+                    const int e = c * kChunk + (k * kThreads + threadIdx.x) * 4;
+                    float x[4], y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    load_quad_vec(trow, e, x);
+                    if (residual) load_quad_vec(drow, e, y);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        t[4 * k + u] = x[u];
+                        d[4 * k + u] = y[u];
+                    }
+                }
+            };
+            load_rows(c_first, ta, da);
+            for (int cc = 0; cc < n_whole; ++cc) {
+                if (cc + 1 < n_whole) load_rows(c_first + cc + 1, tb, db);
+                double r = 0.0, t = 0.0;
+#pragma unroll
+                for (int k = 0; k < kPerThread / 4; ++k) {
                     double res[4], tgt[4];
-                    quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, ek, res, tgt);
-                    sr[cc] += (res[0] + res[1]) + (res[2] + res[3]);
-                    st[cc] += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const double pt = prob_of<MODE>(ta[4 * k + u], T, dec.m_t, dec.Z_t, ek);
+                        tgt[u] = pt;
+                        if (residual) {
+                            const double d = pt - prob_of<MODE>(da[4 * k + u], T, dec.m_d, dec.Z_d, ek);
+                            res[u] = d > 0.0 ? d : 0.0;
+                        } else {
+                            res[u] = pt;
+                        }
+                    }
+                    r += (res[0] + res[1]) + (res[2] + res[3]);
+                    t += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+                }
+                r = wave_sum(r);
+                t = wave_sum(t);
+                if (lane == 0) {
+                    s_part[w][2 * cc] = r;
+                    s_part[w][2 * cc + 1] = t;
+                }
+#pragma unroll
+                for (int u = 0; u < kPerThread; ++u) {
+                    ta[u] = tb[u];
+                    da[u] = db[u];
                 }
             }
         }
+#pragma unroll 1
+        for (int cs = n_whole; cs < n_here; ++cs) {
+            const int e0 = (c_first + cs) * kChunk;
+            double r = 0.0, t = 0.0;
 #pragma unroll
-        for (int cc = 0; cc < kSampleGroup; ++cc) {
-            sr[cc] = wave_sum(sr[cc]);
-            st[cc] = wave_sum(st[cc]);
-        }
-        if (lane == 0) {
-#pragma unroll
-            for (int cc = 0; cc < kSampleGroup; ++cc) {
-                s_part[w][2 * cc] = sr[cc];
-                s_part[w][2 * cc + 1] = st[cc];
+            for (int k = 0; k < kPerThread / 4; ++k) {
+                const int e = e0 + (k * kThreads + threadIdx.x) * 4;
+                double res[4], tgt[4];
+                quad_masses<MODE, RT>(dec, trow, drow, e, V, vec_t, vec_d, T, ek, res, tgt);
+                r += (res[0] + res[1]) + (res[2] + res[3]);
+                t += (tgt[0] + tgt[1]) + (tgt[2] + tgt[3]);
+            }
+            r = wave_sum(r);
+            t = wave_sum(t);
+            if (lane == 0) {
+                s_part[w][2 * cs] = r;
+                s_part[w][2 * cs + 1] = t;
             }
         }
         __syncthreads();
