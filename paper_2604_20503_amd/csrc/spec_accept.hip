@@ -161,7 +161,7 @@ __device__ __forceinline__ ExpConsts exp_consts() {
     ExpConsts k;
     k.floor = -800.0;  // below it exp is 0 in fp64
     k.log2e = 1.4426950408889634074;
-    k.nln2_hi = -6.93147180369123816490e-01;  // high part of ln2: 21 significant bits, so k * hi is exact
+    k.nln2_hi = -6.93147180369123816490e-01;  // high part of ln2: its last 21 bits are zero, so k * hi is exact for |k| < 2^21
     k.nln2_lo = -1.90821492927058770002e-10;
     k.magic = 6755399441055744.0;  // 1.5 * 2^52: adding it rounds to an integer and leaves that integer in the low word
     // the polynomial of degree 10 that equals exp at the 11 Chebyshev nodes of [-ln2/2, ln2/2] (widened by 0.05 %),
