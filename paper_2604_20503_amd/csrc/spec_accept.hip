@@ -250,13 +250,14 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
     if (k < t_n) {
         const int j = t_lo + k, t0 = cu_t[i], t_i = cu_t[i + 1] - t0;
         const long long r = (long long)t0 + j;
-        if (j >= t_i || t0 < 0 || r >= (long long)B * (S_max + 1)) return;  // no such row, or past what the workspace holds
+        // no such row, or past what the workspace or the caller's row map holds (offsets of an invalid call)
+        if (j >= t_i || t0 < 0 || r >= (long long)B * (S_max + 1) || r >= cu_t[B]) return;
         rows = z_target + (size_t)(t_rows ? t_rows[r] : r) * V;
         stat = ws.stat_t + ((size_t)r * nsg + blockIdx.x) * 2;
     } else {
         const int j = d_lo + (k - t_n), d0 = cu_d[i], d_i = cu_d[i + 1] - d0;
         const long long r = (long long)d0 + j;
-        if (j >= d_i || d0 < 0 || r >= (long long)B * S_max) return;
+        if (j >= d_i || d0 < 0 || r >= (long long)B * S_max || r >= cu_d[B]) return;
         rows = z_draft + (size_t)(d_rows ? d_rows[r] : r) * V;
         stat = ws.stat_d + ((size_t)r * nsg + blockIdx.x) * 2;
     }

@@ -199,12 +199,14 @@ def test_logits_mode_masked_vocabulary_and_sharp_temperature(fsr, oracle, B, T):
     assert 0 < n.sum() < b.N_d
 
 
-def test_invalid_request_is_flagged_not_faulted(fsr, oracle):
-    announce("accept invalid request")
-    b = workloads.make_batch(1, with_kv=False)
-    d = DeviceBatch(b, kv=False)
-    acc, nem, em = fsr.spec_accept(d.p_target, d.p_draft, d.draft_tokens, d.u_accept, d.u_sample, d.cu_q, d.cu_d,
-                                   S_max=2)  # requests with 3 and 4 drafts exceed S_max
+@pytest.mark.parametrize("mode", [0, 1])
+def test_invalid_request_is_flagged_not_faulted(fsr, oracle, mode):
+    announce(f"accept invalid request mode={mode}")
+    b = workloads.make_batch(1, with_kv=False, keep_logits=bool(mode))
+    d = DeviceBatch(b, kv=False, logits=bool(mode))
+    rows_t, rows_d = (d.z_target, d.z_draft) if mode else (d.p_target, d.p_draft)
+    acc, nem, em = fsr.spec_accept(rows_t, rows_d, d.draft_tokens, d.u_accept, d.u_sample, d.cu_q, d.cu_d,
+                                   S_max=2, mode=mode)  # requests with 3 and 4 drafts exceed S_max
     torch.cuda.synchronize()
     acc = acc.cpu().numpy()
     assert (acc[b.spec_lens > 2] == -1).all() and (acc[b.spec_lens <= 2] >= 0).all()
