@@ -207,7 +207,6 @@ __device__ __forceinline__ double exp_softmax(double x, const ExpConsts& k) {
     p = fma(p, r, 1.0);
     return ldexp(p, (int)(uint32_t)__builtin_bit_cast(unsigned long long, t));
 }
-__device__ __forceinline__ double exp_softmax(double x) { return exp_softmax(x, exp_consts()); }
 // The constants for a kernel of the given mode: PROBS mode never evaluates exp and gets an empty set.
 template <int MODE>
 __device__ __forceinline__ ExpConsts exp_consts_for() {
@@ -330,23 +329,43 @@ __global__ __launch_bounds__(kThreads) void accept_stats_kernel(
 }
 
 // Combine a row's chunk statistics into (max, partition sum); all lanes of the wave call it.
-__device__ __forceinline__ void combine_stats(const double* __restrict__ stat, int nc, double& m, double& Z) {
+__device__ __forceinline__ void combine_stats(const double* __restrict__ stat, int nc, const ExpConsts& ek, double& m, double& Z) {
     const int lane = threadIdx.x & 63;
     double mm = -INFINITY;
     for (int c = lane; c < nc; c += 64) mm = fmax(mm, stat[c * 2]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mm = fmax(mm, __shfl_xor(mm, o, 64));
     double z = 0.0;
-    for (int c = lane; c < nc; c += 64) z += stat[c * 2 + 1] * exp_softmax(stat[c * 2] - mm);
+    for (int c = lane; c < nc; c += 64) z += stat[c * 2 + 1] * exp_softmax(stat[c * 2] - mm, ek);
     m = mm;
     Z = wave_sum(z);
 }
-// The same by one lane on its own (every lane of the wave works on a different row).
-__device__ __forceinline__ void combine_stats_lane(const double* __restrict__ stat, int nc, double& m, double& Z) {
-    double mm = -INFINITY;
-    for (int c = 0; c < nc; ++c) mm = fmax(mm, stat[c * 2]);
-    double z = 0.0;
-    for (int c = 0; c < nc; ++c) z += stat[c * 2 + 1] * exp_softmax(stat[c * 2] - mm);
+// The same by one lane on its own (every lane of the wave works on a different row): the pairs four at a time, all
+// eight loads of a batch in flight together, folded with a running maximum.
+__device__ __forceinline__ void combine_stats_lane(const double* __restrict__ stat, int nc, const ExpConsts& ek, double& m,
+                                                   double& Z) {
+    double mm = -INFINITY, z = 0.0;
+    for (int c0 = 0; c0 < nc; c0 += 4) {
+        double mc[4], sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = min(c0 + u, nc - 1);
+            mc[u] = stat[c * 2];
+            sc[u] = stat[c * 2 + 1];
+        }
+        double mb = mc[0];
+#pragma unroll
+        for (int u = 1; u < 4; ++u) mb = fmax(mb, c0 + u < nc ? mc[u] : -INFINITY);
+        if (mb > mm) {
+            z = mm == -INFINITY ? 0.0 : z * exp_softmax(mm - mb, ek);
+            mm = mb;
+        }
+        if (mm != -INFINITY) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (c0 + u < nc) z += sc[u] * exp_softmax(mc[u] - mm, ek);
+        }
+    }
     m = mm;
     Z = z;
 }
@@ -446,8 +465,8 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
             x = min(max(draft_tokens[dr], 0), V - 1);
             const double u = (double)u_accept[dr];
             if constexpr (MODE == FSR_LOGITS) {
-                combine_stats_lane(ws.stat_t + (size_t)(t0 + k) * nsg * 2, nsg, m_t, Z_t);
-                combine_stats_lane(ws.stat_d + (size_t)(d0 + k) * nsg * 2, nsg, m_d, Z_d);
+                combine_stats_lane(ws.stat_t + (size_t)(t0 + k) * nsg * 2, nsg, ek, m_t, Z_t);
+                combine_stats_lane(ws.stat_d + (size_t)(d0 + k) * nsg * 2, nsg, ek, m_d, Z_d);
             }
             const double px = prob_of<MODE>(to_float(p_target[(size_t)tr * V + x]), T, m_t, Z_t, ek);
             const double qx = prob_of<MODE>(to_float(p_draft[(size_t)dr * V + x]), T, m_d, Z_d, ek);
@@ -474,7 +493,7 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
     if (n == d_i && t_i == d_i + 1) {
         dec.kind = kCaseTarget;
         dec.t_row = t_rows ? t_rows[t0 + d_i] : t0 + d_i;
-        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nsg * 2, nsg, dec.m_t, dec.Z_t);
+        if constexpr (MODE == FSR_LOGITS) combine_stats(ws.stat_t + (size_t)(t0 + d_i) * nsg * 2, nsg, ek, dec.m_t, dec.Z_t);
     }
     for (int s = n + lane; s <= S_max; s += 64) em[s] = -1;
     if (lane == 0) {
