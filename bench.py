@@ -48,7 +48,7 @@ WORKLOADS = {
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
 
 
-def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=True):
+def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=True, variants=False):
     """Device buffers and a closure running one full step without allocating.  The layers cycle
     through as many distinct KV caches as fit the budget (all 32 at workload 2)."""
     def dev(x, bf16=False):
@@ -137,7 +137,53 @@ def build_step(fsr, torch, b, n_layers, seed, cache_budget_bytes=16e9, use_plan=
 
         calls["accept_logits"] = accept_logits_only
 
-    state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed,
+    extra_layers = 0
+    if variants:  # --variants: the other forms of the same kernels, each timed on its own (not part of the step)
+        # attention over 8-bit caches (E4M3 bytes, one scale per KV head): as many distinct caches as the bf16 ones
+        n8 = int(max(1, min(n_layers, n_caches)))
+        k8 = [torch.randint(0, 120, k0.shape, dtype=torch.uint8, device="cuda", generator=gen) for _ in range(n8)]
+        v8 = [torch.randint(0, 120, k0.shape, dtype=torch.uint8, device="cuda", generator=gen) for _ in range(n8)]
+        sc8 = torch.full((b.H_kv,), 0.02, dtype=torch.float32, device="cuda")
+        out8 = torch.empty_like(q)
+        extra_layers = n_layers
+
+        def attention_kv8_all_layers():
+            if use_plan:
+                fsr.attn_plan(q, k0, bt, ctx, cu_q, scale=b.scale, max_q_len=S_max + 1, plan=plan)
+            for l in range(n_layers):
+                fsr.verify_attention_kv8(q, k8[l % n8], v8[l % n8], sc8, sc8, bt, ctx, cu_q, scale=b.scale, out=out8,
+                                         workspace=ws_attn, max_q_len=S_max + 1, plan=plan)
+
+        # append of the call's own K/V rows (bf16 and quantising), into caches of their own
+        k_new = torch.randn((b.N, b.H_kv, b.D), device="cuda", generator=gen).to(torch.bfloat16)
+        v_new = torch.randn((b.N, b.H_kv, b.D), device="cuda", generator=gen).to(torch.bfloat16)
+        k_app, v_app = k0.clone(), v0.clone()
+
+        def append_only():
+            fsr.kv_append(k_new, v_new, k_app, v_app, bt, ctx, cu_q)
+
+        def append_kv8_only():
+            fsr.kv_append_kv8(k_new, v_new, k8[0], v8[0], sc8, sc8, bt, ctx, cu_q)
+
+        # greedy acceptance (arg-max of every target row) and the restore of the compacted rows to their old places
+        ws_gr = torch.empty(max(256, fsr.accept_workspace_bytes(B=b.B, V=b.V, S_max=S_max, mode=2)), dtype=torch.uint8,
+                            device="cuda")
+        acc_g, nem_g, em_g = torch.empty_like(acc), torch.empty_like(nem), torch.empty_like(em)
+
+        def greedy_only():
+            fsr.spec_accept(p_t, None, toks, None, None, cu_q, cu_d, S_max=S_max, mode=2, accepted_len=acc_g, n_emitted=nem_g,
+                            emitted=em_g, workspace=ws_gr)
+
+        restored = torch.empty_like(out)
+        has_value = torch.empty(b.N, dtype=torch.uint8, device="cuda")
+
+        def restore_only():
+            fsr.prune_restore(packed, prune_out["dst_row"], restored=restored, has_value=has_value)
+
+        calls.update(attention_kv8=attention_kv8_all_layers, kv_append=append_only, kv_append_kv8=append_kv8_only,
+                     greedy_accept=greedy_only, prune_restore=restore_only)
+
+    state = dict(q=q, k0=k0, v0=v0, out=out, acc=acc, nem=nem, em=em, prune=prune_out, packed=packed, variant_layers=extra_layers,
                  n_caches=n_caches, kv_bytes=kv_bytes, k_caches=k_caches, v_caches=v_caches,
                  dev=dict(bt=bt, ctx=ctx, spec=spec, cu_q=cu_q, cu_d=cu_d, p_t=p_t, p_d=p_d, toks=toks, u_a=u_a, u_s=u_s),
                  calls=calls)
@@ -183,6 +229,19 @@ def kernel_figures(b, st, times_us):
             f"accept_sample_kernel, T = 1; normalising every row of the call would read {all_rows_bytes} bytes; "
             f"this call reads {read_bytes} bytes; "
             f"not part of the timed step")
+    if "attention_kv8" in times_us:
+        L = st["variant_layers"]
+        kv8_bytes = b.attention_bytes() - b.kv_tokens() * b.H_kv * b.D * 2   # K and V at one byte per element
+        extra["verify_attention_kv8"] = fig(times_us["attention_kv8"] / L, kv8_bytes, 1,
+                                            "verify_attention over E4M3 caches, per layer call (planned like the bf16 call unless --no-plan); not part of the timed step")
+        rows_bytes = 2 * b.N * b.H_kv * b.D * 2
+        extra["kv_append"] = fig(times_us["kv_append"], 2 * rows_bytes, 1, "kv_append_kernel: the call's bf16 K and V rows in, the same bytes into the pages")
+        extra["kv_append_kv8"] = fig(times_us["kv_append_kv8"], rows_bytes + rows_bytes // 2, 1,
+                                     "kv_append_kv8_kernel: bf16 rows in, E4M3 bytes into the pages")
+        extra["greedy_accept"] = fig(times_us["greedy_accept"], b.N * 4 * b.V + 4 * int(d.sum()), 2,
+                                     "greedy_argmax_kernel + greedy_decide_kernel: every target row of the call once")
+        extra["prune_restore"] = fig(times_us["prune_restore"], (n_new + b.N) * row_bytes + 5 * b.N, 1,
+                                     "restore_rows_kernel: surviving rows back to their old places, filler elsewhere")
     return {
         **extra,
         "spec_accept": fig(times_us["accept"], accept_bytes, 2, "accept_decide_kernel + accept_sample_kernel"),
@@ -452,6 +511,9 @@ def main():
                          "stand-in drafter on a stream that owns those N (adds an \"overlap\" object to the JSON line)")
     ap.add_argument("--logits", action="store_true",
                     help="also time spec_accept in LOGITS mode on the step's rows (reported under kernels.spec_accept_logits)")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the other forms of the kernels on the step's shapes: attention over 8-bit caches, "
+                         "K/V append, greedy acceptance, row restore (reported under kernels)")
     ap.add_argument("--probe", action="store_true", help="time only the plain-read probe (three access patterns) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that hardware byte counters of a "
@@ -521,7 +583,8 @@ def main():
         print(json.dumps(result))
         return
 
-    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=not args.no_plan)
+    step, attn_only, tail, st = build_step(fsr, torch, b, args.layers, seed=2002, use_plan=not args.no_plan,
+                                           variants=args.variants)
     stream = torch.cuda.Stream()
     graph = None
     with torch.cuda.stream(stream):

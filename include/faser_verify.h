@@ -240,6 +240,18 @@ int fsr_verify_attention_kv8(const void* q, const void* k_cache, const void* v_c
                              void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * fsr_verify_attention_kv8 reading a per-step schedule (Sec. 3.1: the lengths and block tables of a verification
+ * step are the same for every layer): `plan` is a buffer that fsr_attn_plan has filled for the same *p, exactly as
+ * for fsr_verify_attention_planned -- the schedule does not depend on how the caches are stored, so one plan serves
+ * bf16 and 8-bit caches alike.  Results are bit-identical to fsr_verify_attention_kv8; errors as for the two calls
+ * it combines.
+ */
+int fsr_verify_attention_kv8_planned(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                                     const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
+                                     const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p /*host*/,
+                                     const void* plan, void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Cache append (Sec. 2.1 / Sec. 3.1: the drafted tokens of a request enter the target model as
  * new positions behind its cached context).  Row j of request i (row cu_q[i] + j of k_new /
  * v_new) is the token at logical position ctx_lens[i] + j: its key and value vectors are copied,

@@ -23,7 +23,7 @@ EWS = -4  # FSR_EWS: workspace missing, too small, or (binding only) still in us
 
 SYMBOLS = [
     "fsr_last_error", "fsr_version", "fsr_attn_workspace_bytes", "fsr_attn_path", "fsr_attn_plan_bytes", "fsr_attn_plan",
-    "fsr_verify_attention_planned", "fsr_verify_attention_static", "fsr_static_scratch_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_kv_append", "fsr_kv_append_kv8",
+    "fsr_verify_attention_planned", "fsr_verify_attention_static", "fsr_static_scratch_bytes", "fsr_verify_attention", "fsr_verify_attention_kv8", "fsr_verify_attention_kv8_planned", "fsr_kv_append", "fsr_kv_append_kv8",
     "fsr_accept_workspace_bytes", "fsr_spec_accept", "fsr_prune_compact", "fsr_prune_restore",
     "fsr_prune_scatter", "fsr_survivor_mask", "fsr_survivor_compact", "fsr_topk_rank_check", "fsr_frontier_init", "fsr_frontier_plan", "fsr_frontier_commit",
     "fsr_hbm_read_probe",
@@ -255,8 +255,9 @@ def verify_attention_static(q, k_cache, v_cache, block_tables, ctx_lens, cu_q, *
 
 
 def verify_attention_kv8(q, k_cache, v_cache, k_scale, v_scale, block_tables, ctx_lens, cu_q, *, scale, out=None, lse=None,
-                         out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR):
-    """fsr_verify_attention_kv8: caches are uint8 tensors of E4M3 bytes, k_scale / v_scale [H_kv] float32."""
+                         out_dtype=None, workspace=None, max_q_len=0, max_workgroups=0, kv_layout=KV_HEAD_MAJOR, plan=None):
+    """fsr_verify_attention_kv8: caches are uint8 tensors of E4M3 bytes, k_scale / v_scale [H_kv] float32.
+    plan: buffer from attn_plan for the same shapes and metadata -> fsr_verify_attention_kv8_planned."""
     lib = load_library()
     B = ctx_lens.shape[0]
     out_dtype = out_dtype or (out.dtype if out is not None else q.dtype)
@@ -274,6 +275,14 @@ def verify_attention_kv8(q, k_cache, v_cache, k_scale, v_scale, block_tables, ct
     if workspace is None and need.value:
         workspace = torch.empty(need.value, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if plan is not None:
+        _check(lib.fsr_verify_attention_kv8_planned(
+            _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
+            _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),
+            _ptr(block_tables, torch.int32, "block_tables"), _ptr(ctx_lens, torch.int32, "ctx_lens"),
+            _ptr(cu_q, torch.int32, "cu_q"), _ptr(out, name="out"), _ptr(lse, torch.float32, "lse"), ctypes.byref(p),
+            _ptr(plan, name="plan"), _ptr(workspace, name="workspace"), ctypes.c_size_t(ws_bytes), _stream()))
+        return out, lse
     _check(lib.fsr_verify_attention_kv8(
         _ptr(q, name="q"), _ptr(k_cache, name="k_cache"), _ptr(v_cache, name="v_cache"),
         _ptr(k_scale, torch.float32, "k_scale"), _ptr(v_scale, torch.float32, "v_scale"),

@@ -1762,6 +1762,15 @@ extern "C" int fsr_verify_attention_planned(const void* q, const void* k_cache, 
                           ws_bytes, kMaxShares, stream, "fsr_verify_attention_planned");
 }
 
+extern "C" int fsr_verify_attention_kv8_planned(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                                                const float* v_scale, const int32_t* block_tables, const int32_t* ctx_lens,
+                                                const int32_t* cu_q, void* out, float* lse, const fsr_attn_params* p,
+                                                const void* plan, void* workspace, size_t ws_bytes, void* stream) {
+    if (!plan) return fail(FSR_EINVAL, "fsr_verify_attention_kv8_planned: plan is null");
+    return attention_call(q, k_cache, v_cache, k_scale, v_scale, true, block_tables, ctx_lens, cu_q, out, lse, p, plan, workspace,
+                          ws_bytes, kMaxShares, stream, "fsr_verify_attention_kv8_planned");
+}
+
 // ---------------------------------------------------------------------------------------
 // fsr_verify_attention_static: the same call for callers that cannot allocate (or be handed) a
 // workspace.  The partial slots and arrival words live in a file-scope device array, laid out for

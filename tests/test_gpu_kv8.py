@@ -42,11 +42,17 @@ def run_pair(fsr, oracle, b, k8, v8, k_scale, v_scale, out_dtype, token_major=Fa
                                                  H_q=b.H_q, H_kv=b.H_kv, D=b.D, P=b.P, scale=b.scale)
     kd, vd = (np.ascontiguousarray(np.swapaxes(c, 1, 2)) if token_major else c for c in (k8, v8))
     lse = torch.empty(b.N, b.H_q, dtype=torch.float32, device="cuda")
-    out, _ = fsr.verify_attention_kv8(dev(b.q, True), dev(kd), dev(vd), dev(k_scale), dev(v_scale), dev(b.block_tables),
-                                      dev(b.ctx_lens), dev(b.cu_q), scale=b.scale, out_dtype=out_dtype, lse=lse,
-                                      max_q_len=b.S_max + 1 if max_q_len is None else max_q_len,
-                                      kv_layout=fsr.binding.KV_TOKEN_MAJOR if token_major else fsr.binding.KV_HEAD_MAJOR)
+    args = (dev(b.q, True), dev(kd), dev(vd), dev(k_scale), dev(v_scale), dev(b.block_tables), dev(b.ctx_lens), dev(b.cu_q))
+    kw = dict(scale=b.scale, out_dtype=out_dtype, max_q_len=b.S_max + 1 if max_q_len is None else max_q_len,
+              kv_layout=fsr.binding.KV_TOKEN_MAJOR if token_major else fsr.binding.KV_HEAD_MAJOR)
+    out, _ = fsr.verify_attention_kv8(*args, lse=lse, **kw)
+    # the same call reading a per-step plan (one plan serves bf16 and 8-bit caches): bit-identical
+    plan = fsr.attn_plan(args[0], args[1], args[5], args[6], args[7], **kw)
+    lse_p = torch.full_like(lse, float("nan"))
+    out_p, _ = fsr.verify_attention_kv8(*args, lse=lse_p, plan=plan, **kw)
     torch.cuda.synchronize()
+    bits = torch.int16 if out.dtype == torch.bfloat16 else torch.int32
+    assert torch.equal(out.view(bits), out_p.view(bits)) and torch.equal(lse.view(torch.int32), lse_p.view(torch.int32))
     err = check_attention(out, o_ref, "bf16", b.N)
     np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=2e-5, atol=2e-5)
     return err
