@@ -237,9 +237,9 @@ def kernel_figures(b, st, times_us):
         rows_bytes = 2 * b.N * b.H_kv * b.D * 2
         extra["kv_append"] = fig(times_us["kv_append"], 2 * rows_bytes, 1, "kv_append_kernel: the call's bf16 K and V rows in, the same bytes into the pages")
         extra["kv_append_kv8"] = fig(times_us["kv_append_kv8"], rows_bytes + rows_bytes // 2, 1,
-                                     "kv_append_kv8_kernel: bf16 rows in, E4M3 bytes into the pages")
-        extra["greedy_accept"] = fig(times_us["greedy_accept"], b.N * 4 * b.V + 4 * int(d.sum()), 2,
-                                     "greedy_argmax_kernel + greedy_decide_kernel: every target row of the call once")
+                                     "kv_append8_kernel: bf16 rows in, E4M3 bytes into the pages")
+        extra["greedy_accept"] = fig(times_us["greedy_accept"], b.N * 4 * b.V + 4 * int(d.sum()), 3,
+                                     "greedy_init_kernel + greedy_argmax_kernel + greedy_decide_kernel: every target row of the call once")
         extra["prune_restore"] = fig(times_us["prune_restore"], (n_new + b.N) * row_bytes + 5 * b.N, 1,
                                      "restore_rows_kernel: surviving rows back to their old places, filler elsewhere")
     return {
